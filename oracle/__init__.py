@@ -1,0 +1,152 @@
+"""Python face of the CPU oracle (oracle/tokfilt_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's cpu-baseline leg may import this package.
+It knows nothing about the HIP library and shares nothing with it.
+
+Every function takes torch CPU tensors or numpy arrays (bf16 tensors are widened to float
+exactly) in the [B, H, n, d] layout and returns numpy arrays.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "tokfilt_oracle.c")
+_LIB = os.path.join(_HERE, "libtokfilt_oracle.so")
+
+FUSE_EQ2, FUSE_INVVAR, FUSE_KEY_ONLY, FUSE_VALUE_ONLY = 0, 1, 2, 3
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (plain -O2, OpenMP over (batch, head) only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fopenmp", "-fPIC", "-shared",
+                               "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        i64, dbl, vp = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
+        lib.tfo_num_threads.restype = ctypes.c_int
+        lib.tfo_anchor_cosine.argtypes = [vp, i64, i64, i64, i64, vp, vp]
+        lib.tfo_fuse.argtypes = [vp, vp, i64, i64, i64, ctypes.c_int, vp, vp]
+        lib.tfo_keep_count.argtypes = [i64, dbl]
+        lib.tfo_keep_count.restype = i64
+        lib.tfo_select.argtypes = [vp, i64, i64, i64, i64, vp, vp, vp]
+        lib.tfo_attend.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, vp, i64, dbl, vp]
+        lib.tfo_attend_rows.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, vp, i64, dbl,
+                                        vp, i64, vp]
+        _lib = lib
+    return _lib
+
+
+def num_threads() -> int:
+    return int(_load().tfo_num_threads())
+
+
+def _f32(x) -> np.ndarray:
+    """Contiguous float32 numpy view/copy of a torch tensor or array (bf16 widened exactly)."""
+    if hasattr(x, "detach"):
+        x = x.detach().cpu().float().contiguous().numpy()
+    return np.ascontiguousarray(x, dtype=np.float32)
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def anchor_cosine(x, return_anchors: bool = False):
+    """Per-head cosine of each token's row with the mean of the rows before it.
+    x: [B, H, n, d] -> cos [B, H, n] (float64); optionally the anchors [B, H, n, d]."""
+    xa = _f32(x)
+    B, H, n, d = xa.shape
+    cosv = np.empty((B, H, n), dtype=np.float64)
+    anchors = np.empty((B, H, n, d), dtype=np.float64) if return_anchors else None
+    _load().tfo_anchor_cosine(_p(xa), B, H, n, d, _p(cosv),
+                              _p(anchors) if return_anchors else None)
+    return (cosv, anchors) if return_anchors else cosv
+
+
+def fuse(cos_k, cos_v, mode: int = FUSE_EQ2, return_stats: bool = False):
+    """Across-head mean/variance and variance-aware fusion.
+    cos_k, cos_v: [B, H, n] -> S [B, n]; stats [B, n, 5] = (s_k, s_v, var_k, var_v, alpha)."""
+    ck = np.ascontiguousarray(cos_k, dtype=np.float64)
+    cv = np.ascontiguousarray(cos_v, dtype=np.float64)
+    B, H, n = ck.shape
+    S = np.empty((B, n), dtype=np.float64)
+    stats = np.empty((B, n, 5), dtype=np.float64) if return_stats else None
+    _load().tfo_fuse(_p(ck), _p(cv), B, H, n, int(mode), _p(S),
+                     _p(stats) if return_stats else None)
+    return (S, stats) if return_stats else S
+
+
+def keep_count(n: int, ratio: float) -> int:
+    return int(_load().tfo_keep_count(int(n), float(ratio)))
+
+
+def select(scores, ratio: float, warmup: int = 1):
+    """Keep decision at an exact count.  scores: [B, n] (rounded to float32 first, the
+    precision the decision is defined in).  Returns keep [B, n] uint8, kept_idx [B, m]
+    int32, tau [B] float32."""
+    s32 = np.ascontiguousarray(np.asarray(scores, dtype=np.float64).astype(np.float32))
+    B, n = s32.shape
+    m = keep_count(n, ratio)
+    keep = np.empty((B, n), dtype=np.uint8)
+    idx = np.empty((B, m), dtype=np.int32)
+    tau = np.empty((B,), dtype=np.float32)
+    _load().tfo_select(_p(s32), B, n, m, int(warmup), _p(keep), _p(idx), _p(tau))
+    return keep, idx, tau
+
+
+def _scale(d, scale):
+    return float(scale) if scale else 1.0 / float(np.sqrt(d))
+
+
+def attend(q, k, v, kept_idx, scale: float = 0.0):
+    """Causal softmax attention among kept tokens; zero rows elsewhere.  -> O [B, Hq, n, d]."""
+    qa, ka, va = _f32(q), _f32(k), _f32(v)
+    B, Hq, n, d = qa.shape
+    Hkv = ka.shape[1]
+    idx = np.ascontiguousarray(kept_idx, dtype=np.int32)
+    m = idx.shape[1]
+    O = np.empty((B, Hq, n, d), dtype=np.float64)
+    _load().tfo_attend(_p(qa), _p(ka), _p(va), B, Hq, Hkv, n, d, _p(idx), m,
+                       _scale(d, scale), _p(O))
+    return O
+
+
+def attend_rows(q, k, v, kept_idx, rows, scale: float = 0.0):
+    """Selected output rows only.  rows: [R, 3] = (b, hq, kept rank).  -> [R, d]."""
+    qa, ka, va = _f32(q), _f32(k), _f32(v)
+    B, Hq, n, d = qa.shape
+    Hkv = ka.shape[1]
+    idx = np.ascontiguousarray(kept_idx, dtype=np.int32)
+    m = idx.shape[1]
+    r = np.ascontiguousarray(rows, dtype=np.int32)
+    out = np.empty((r.shape[0], d), dtype=np.float64)
+    _load().tfo_attend_rows(_p(qa), _p(ka), _p(va), B, Hq, Hkv, n, d, _p(idx), m,
+                            _scale(d, scale), _p(r), r.shape[0], _p(out))
+    return out
+
+
+def filtered_attention(q, k, v, ratio: float, warmup: int = 1, mode: int = FUSE_EQ2,
+                       scale: float = 0.0, with_attention: bool = True):
+    """The whole path: score -> fuse -> select -> attend.  Returns a dict of numpy arrays."""
+    ck = anchor_cosine(k)
+    cv = anchor_cosine(v)
+    S = fuse(ck, cv, mode)
+    keep, idx, tau = select(S, ratio, warmup)
+    out = {"sim_k": ck, "sim_v": cv, "fused": S, "keep": keep, "kept_idx": idx, "tau": tau}
+    if with_attention:
+        out["O"] = attend(q, k, v, idx, scale)
+    return out

@@ -1,0 +1,286 @@
+/*
+ * CPU oracle for the Token Filtering hot path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, double-precision restatement of what the paper defines, used to check the
+ * HIP library.  Nothing in the product path may call into this file; it shares no code,
+ * header or table with the GPU sources.
+ *
+ * Paper passages followed (arxiv 2512.07090, "Leveraging KV Similarity for Online Structured
+ * Pruning in LLMs"):
+ *   - anchor = mean of all previous keys / values, one vector per head:
+ *       Algorithm 1 (anchor lines), Section 3.2 paragraph on the anchor key;
+ *   - per-head cosine similarity between anchor and current key / value: Algorithm 1,
+ *       Section 3.2 (similarity computed per head, then averaged over heads);
+ *   - mean and variance over heads, variance-aware fusion: Algorithm 1, Eq. 2;
+ *   - skip decision "skip iff S_KV > tau": Algorithm 1 last line, Section 3.3;
+ *   - a skipped token's attention output is zero: Section 3.2, paragraph after Algorithm 1;
+ *   - attention over the remaining tokens is ordinary causal softmax attention.
+ *
+ * Readings where the paper is silent or inconsistent (each is also listed in the design
+ * document):
+ *   - the anchor of token t excludes token t (prose: "previous"); token 0 has a zero anchor;
+ *   - cosine denominator is max(|a| |x|, 1e-8) and the cosine is clamped to [-1, 1];
+ *   - the variance is the population variance across heads for one token; 1e-12 is added to
+ *     each variance before it is used in alpha;
+ *   - fusion mode 0 is alpha exactly as printed in Eq. 2 / Algorithm 1, mode 1 is the
+ *     inverse-variance weighting the prose describes, modes 2 / 3 are key-only / value-only;
+ *   - the threshold is realised as an exact count: the m = n - floor(r n + 1e-6) tokens with
+ *     the lowest score are kept, ties broken towards the lower index, after force-keeping
+ *     the first W tokens (warm-up); the decision is taken on the score rounded to float,
+ *     the precision the GPU path decides in;
+ *   - filtered tokens are neither queries nor keys.
+ *
+ * Parity pins live in tests/test_oracle_pins.py.  Unpinned by the paper (fixed only by the
+ * readings above): fusion direction, warm-up length, the two epsilons, the tie-break.
+ *
+ * Layout everywhere: X[b][h][t][c], c contiguous, float inputs (bf16 inputs are widened
+ * exactly by the caller), double arithmetic, double outputs unless stated.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define TFO_EPS_COS 1e-8
+#define TFO_EPS_VAR 1e-12
+
+int tfo_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Anchor (Algorithm 1, anchor lines; Section 3.2): for each (b, h, t) the mean of rows
+ * 0..t-1 of X[b][h], and the cosine similarity of that mean with row t.
+ * cosv: [B][H][n].  anchors (optional, may be NULL): [B][H][n][d], the means themselves. */
+void tfo_anchor_cosine(const float *X, int64_t B, int64_t H, int64_t n, int64_t d,
+                       double *cosv, double *anchors)
+{
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int64_t b = 0; b < B; ++b) {
+        for (int64_t h = 0; h < H; ++h) {
+            double *sum = (double *)calloc((size_t)d, sizeof(double));
+            double *anchor = (double *)calloc((size_t)d, sizeof(double));
+            const float *xbh = X + ((b * H + h) * n) * d;
+            for (int64_t t = 0; t < n; ++t) {
+                const float *x = xbh + t * d;
+                for (int64_t c = 0; c < d; ++c)
+                    anchor[c] = (t == 0) ? 0.0 : sum[c] / (double)t;
+                if (anchors)
+                    memcpy(anchors + (((b * H + h) * n) + t) * d, anchor,
+                           (size_t)d * sizeof(double));
+                double dot = 0.0, na = 0.0, nx = 0.0;
+                for (int64_t c = 0; c < d; ++c) {
+                    double xc = (double)x[c];
+                    dot += anchor[c] * xc;
+                    na += anchor[c] * anchor[c];
+                    nx += xc * xc;
+                }
+                double den = sqrt(na) * sqrt(nx);
+                if (den < TFO_EPS_COS)
+                    den = TFO_EPS_COS;
+                double cs = dot / den;
+                if (cs > 1.0)
+                    cs = 1.0;
+                if (cs < -1.0)
+                    cs = -1.0;
+                cosv[(b * H + h) * n + t] = cs;
+                for (int64_t c = 0; c < d; ++c)
+                    sum[c] += (double)x[c];
+            }
+            free(sum);
+            free(anchor);
+        }
+    }
+}
+
+/* Head statistics and fusion (Algorithm 1 mean/var lines; Eq. 2).
+ * cK, cV: [B][H][n] per-head cosines.  mode: 0 Eq. 2 as printed, 1 inverse-variance as in
+ * the prose, 2 key only, 3 value only.
+ * S: [B][n].  stats (optional): [B][n][5] = s_k, s_v, var_k, var_v, alpha. */
+void tfo_fuse(const double *cK, const double *cV, int64_t B, int64_t H, int64_t n, int mode,
+              double *S, double *stats)
+{
+    for (int64_t b = 0; b < B; ++b) {
+        for (int64_t t = 0; t < n; ++t) {
+            double sk = 0.0, sv = 0.0;
+            for (int64_t h = 0; h < H; ++h) {
+                sk += cK[(b * H + h) * n + t];
+                sv += cV[(b * H + h) * n + t];
+            }
+            sk /= (double)H;
+            sv /= (double)H;
+            double vk = 0.0, vv = 0.0;
+            for (int64_t h = 0; h < H; ++h) {
+                double dk = cK[(b * H + h) * n + t] - sk;
+                double dv = cV[(b * H + h) * n + t] - sv;
+                vk += dk * dk;
+                vv += dv * dv;
+            }
+            vk /= (double)H;
+            vv /= (double)H;
+            double ek = vk + TFO_EPS_VAR, ev = vv + TFO_EPS_VAR;
+            double alpha;
+            if (mode == 0)
+                alpha = (1.0 / ev) / (1.0 / ek + 1.0 / ev); /* Eq. 2 exactly as printed */
+            else if (mode == 1)
+                alpha = (1.0 / ek) / (1.0 / ek + 1.0 / ev); /* weight on the steadier side */
+            else if (mode == 2)
+                alpha = 1.0;
+            else
+                alpha = 0.0;
+            S[b * n + t] = alpha * sk + (1.0 - alpha) * sv;
+            if (stats) {
+                double *st = stats + (b * n + t) * 5;
+                st[0] = sk;
+                st[1] = sv;
+                st[2] = vk;
+                st[3] = vv;
+                st[4] = alpha;
+            }
+        }
+    }
+}
+
+/* Number of kept tokens for pruning ratio r over n tokens. */
+int64_t tfo_keep_count(int64_t n, double r)
+{
+    return n - (int64_t)floor(r * (double)n + 1e-6);
+}
+
+typedef struct {
+    float s;
+    int32_t idx;
+} tfo_pair;
+
+static int tfo_pair_cmp(const void *a, const void *b)
+{
+    const tfo_pair *pa = (const tfo_pair *)a, *pb = (const tfo_pair *)b;
+    if (pa->s < pb->s)
+        return -1;
+    if (pa->s > pb->s)
+        return 1;
+    return (pa->idx > pb->idx) - (pa->idx < pb->idx);
+}
+
+/* Decision (Algorithm 1 last line, with the exact-count reading): per batch row keep the
+ * first min(W, m) tokens, then the m - min(W, m) remaining tokens with the lowest score
+ * (ties: lower index first).  S32: [B][n] scores already rounded to float.
+ * keep: [B][n] 0/1.  kept_idx: [B][m] ascending positions.  tau: [B] = largest score among
+ * kept non-forced tokens; +inf if nothing is filtered, -inf if no non-forced token is kept. */
+void tfo_select(const float *S32, int64_t B, int64_t n, int64_t m, int64_t W, uint8_t *keep,
+                int32_t *kept_idx, float *tau)
+{
+    for (int64_t b = 0; b < B; ++b) {
+        const float *s = S32 + b * n;
+        uint8_t *kp = keep + b * n;
+        int64_t forced = W < m ? W : m;
+        if (forced < 0)
+            forced = 0;
+        memset(kp, 0, (size_t)n);
+        for (int64_t t = 0; t < forced; ++t)
+            kp[t] = 1;
+        int64_t rest = n - forced, want = m - forced;
+        tfo_pair *p = (tfo_pair *)malloc((size_t)(rest > 0 ? rest : 1) * sizeof(tfo_pair));
+        for (int64_t t = forced; t < n; ++t) {
+            p[t - forced].s = s[t];
+            p[t - forced].idx = (int32_t)t;
+        }
+        qsort(p, (size_t)rest, sizeof(tfo_pair), tfo_pair_cmp);
+        float tb;
+        if (m >= n)
+            tb = INFINITY;
+        else if (want <= 0)
+            tb = -INFINITY;
+        else
+            tb = p[want - 1].s;
+        for (int64_t i = 0; i < want; ++i)
+            kp[p[i].idx] = 1;
+        free(p);
+        tau[b] = tb;
+        int64_t c = 0;
+        for (int64_t t = 0; t < n; ++t)
+            if (kp[t])
+                kept_idx[b * m + c++] = (int32_t)t;
+    }
+}
+
+/* One output row of causal softmax attention restricted to the kept tokens: query at kept
+ * rank i of (b, hq) attends kept ranks 0..i of kv head hq / (Hq / Hkv).  out: [d]. */
+static void tfo_attend_one(const float *Q, const float *K, const float *V, int64_t Hq,
+                           int64_t Hkv, int64_t n, int64_t d, const int32_t *idx, int64_t i,
+                           int64_t b, int64_t hq, double scale, double *logits, double *out)
+{
+    int64_t hk = hq / (Hq / Hkv);
+    const float *q = Q + (((b * Hq + hq) * n) + idx[i]) * d;
+    const float *Kbh = K + ((b * Hkv + hk) * n) * d;
+    const float *Vbh = V + ((b * Hkv + hk) * n) * d;
+    double mx = -INFINITY;
+    for (int64_t j = 0; j <= i; ++j) {
+        const float *k = Kbh + (int64_t)idx[j] * d;
+        double acc = 0.0;
+        for (int64_t c = 0; c < d; ++c)
+            acc += (double)q[c] * (double)k[c];
+        logits[j] = acc * scale;
+        if (logits[j] > mx)
+            mx = logits[j];
+    }
+    double z = 0.0;
+    for (int64_t j = 0; j <= i; ++j) {
+        logits[j] = exp(logits[j] - mx);
+        z += logits[j];
+    }
+    for (int64_t c = 0; c < d; ++c)
+        out[c] = 0.0;
+    for (int64_t j = 0; j <= i; ++j) {
+        const float *v = Vbh + (int64_t)idx[j] * d;
+        double wj = logits[j] / z;
+        for (int64_t c = 0; c < d; ++c)
+            out[c] += wj * (double)v[c];
+    }
+}
+
+/* Attention over kept tokens for the whole layer (Section 3.2: zero output for skipped
+ * tokens; standard causal attention otherwise).  Q: [B][Hq][n][d]; K, V: [B][Hkv][n][d];
+ * kept_idx: [B][m]; O: [B][Hq][n][d], rows of filtered positions are exactly zero. */
+void tfo_attend(const float *Q, const float *K, const float *V, int64_t B, int64_t Hq,
+                int64_t Hkv, int64_t n, int64_t d, const int32_t *kept_idx, int64_t m,
+                double scale, double *O)
+{
+    memset(O, 0, (size_t)(B * Hq * n * d) * sizeof(double));
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int64_t b = 0; b < B; ++b) {
+        for (int64_t hq = 0; hq < Hq; ++hq) {
+            double *logits = (double *)malloc((size_t)(m > 0 ? m : 1) * sizeof(double));
+            const int32_t *idx = kept_idx + b * m;
+            for (int64_t i = 0; i < m; ++i)
+                tfo_attend_one(Q, K, V, Hq, Hkv, n, d, idx, i, b, hq, scale, logits,
+                               O + (((b * Hq + hq) * n) + idx[i]) * d);
+            free(logits);
+        }
+    }
+}
+
+/* The same definition for a list of sampled output rows: rows[r] = (b, hq, kept rank i);
+ * out: [R][d].  Used where the full layer is too large to recompute on the CPU. */
+void tfo_attend_rows(const float *Q, const float *K, const float *V, int64_t B, int64_t Hq,
+                     int64_t Hkv, int64_t n, int64_t d, const int32_t *kept_idx, int64_t m,
+                     double scale, const int32_t *rows, int64_t R, double *out)
+{
+    (void)B;
+#pragma omp parallel for schedule(dynamic)
+    for (int64_t r = 0; r < R; ++r) {
+        int64_t b = rows[3 * r], hq = rows[3 * r + 1], i = rows[3 * r + 2];
+        double *logits = (double *)malloc((size_t)(i + 1) * sizeof(double));
+        tfo_attend_one(Q, K, V, Hq, Hkv, n, d, kept_idx + b * m, i, b, hq, scale, logits,
+                       out + r * d);
+        free(logits);
+    }
+}

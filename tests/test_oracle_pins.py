@@ -1,0 +1,326 @@
+"""Pins for the CPU oracle: closed forms, hand-worked fixtures, invariants, brute force and
+library routines.  No GPU.  A plausible slip in the oracle (inclusive instead of exclusive
+anchor, dropped 1/t, population/sample variance mix-up in alpha, wrong tie-break, K/V swapped
+in attention, wrong GQA head map, missing causal mask) fails at least one test here."""
+import math
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2512_07090_amd import synth
+
+
+def _load_table(path):
+    rows = []
+    with open(path) as f:
+        for line in f:
+            line = line.strip()
+            if line and not line.startswith("#"):
+                rows.append([float(x) for x in line.split()])
+    return np.array(rows)
+
+
+# ------------------------------------------------------------------ anchor / prefix mean
+
+def test_anchor_golden_closed_form(golden_dir):
+    tab = _load_table(os.path.join(golden_dir, "cosine_closed_forms.txt"))
+    x = tab[:, 1:3].astype(np.float32).reshape(1, 1, 4, 2)
+    cosv, anchors = oracle.anchor_cosine(x, return_anchors=True)
+    np.testing.assert_allclose(anchors[0, 0], tab[:, 3:5], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(cosv[0, 0], tab[:, 5], rtol=0, atol=1e-15)
+
+
+def test_anchor_brute_force_prefix_mean():
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((2, 3, 9, 5)).astype(np.float32)
+    cosv, anchors = oracle.anchor_cosine(x, return_anchors=True)
+    xd = x.astype(np.float64)
+    for b in range(2):
+        for h in range(3):
+            for t in range(9):
+                ref = xd[b, h, :t].mean(axis=0) if t else np.zeros(5)   # O(n^2) recomputation
+                np.testing.assert_allclose(anchors[b, h, t], ref, rtol=0, atol=1e-14)
+                if t:
+                    c = np.dot(ref, xd[b, h, t]) / (np.linalg.norm(ref) * np.linalg.norm(xd[b, h, t]))
+                    assert abs(cosv[b, h, t] - c) < 1e-13
+                else:
+                    assert cosv[b, h, t] == 0.0
+
+
+def test_anchor_two_tokens():
+    x = np.array([[3.0, 4.0], [4.0, 3.0]], dtype=np.float32).reshape(1, 1, 2, 2)
+    cosv, anchors = oracle.anchor_cosine(x, return_anchors=True)
+    np.testing.assert_array_equal(anchors[0, 0, 1], [3.0, 4.0])      # anchor at t=1 is x_0
+    assert abs(cosv[0, 0, 1] - 24.0 / 25.0) < 1e-15
+
+
+def test_cosine_range_and_identical_tokens():
+    q, k, v, _ = synth.make_random_qkv(2, 4, 4, 64, 16, seed=3)
+    for x in (k, v):
+        c = oracle.anchor_cosine(x)
+        assert np.all(c <= 1.0) and np.all(c >= -1.0)
+        assert np.all(c[:, :, 0] == 0.0)
+    row = np.random.default_rng(0).standard_normal(16).astype(np.float32)
+    same = np.broadcast_to(row, (1, 2, 10, 16)).copy()
+    c = oracle.anchor_cosine(same)
+    assert np.all(c[:, :, 0] == 0.0)
+    np.testing.assert_allclose(c[:, :, 1:], 1.0, rtol=0, atol=1e-15)   # scores 1 after the first
+
+
+def test_cosine_opposite_orthogonal_and_zero_rows():
+    # x_t = -(mean of previous) gives -1
+    x = np.zeros((1, 1, 3, 4), dtype=np.float32)
+    x[0, 0, 0] = [1, 2, 0, 0]
+    x[0, 0, 1] = [3, 0, 0, 0]
+    x[0, 0, 2] = [-2, -1, 0, 0]       # -(x0 + x1)/2
+    c = oracle.anchor_cosine(x)
+    assert abs(c[0, 0, 2] + 1.0) < 1e-15
+    # orthogonal basis vectors give 0; an all-zero row gives 0 through the guard
+    e = np.zeros((1, 1, 4, 4), dtype=np.float32)
+    e[0, 0, 0, 0] = e[0, 0, 1, 1] = e[0, 0, 2, 2] = 1.0
+    c = oracle.anchor_cosine(e)
+    np.testing.assert_array_equal(c[0, 0], [0, 0, 0, 0])
+
+
+def test_cosine_scale_invariance_and_mean_vs_sum():
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((1, 2, 33, 8)).astype(np.float32)
+    c1 = oracle.anchor_cosine(x)
+    c2 = oracle.anchor_cosine(x * np.float32(4.0))          # power of two: exact rescale
+    np.testing.assert_allclose(c1, c2, rtol=0, atol=1e-14)
+    xd = x.astype(np.float64)
+    sums = np.cumsum(xd, axis=2) - xd                        # exclusive prefix SUM
+    num = (sums * xd).sum(-1)
+    den = np.linalg.norm(sums, axis=-1) * np.linalg.norm(xd, axis=-1)
+    ref = np.where(den > 0, num / np.where(den > 0, den, 1), 0.0)
+    np.testing.assert_allclose(c1, ref, rtol=0, atol=1e-13)  # cos(mean, x) == cos(sum, x)
+
+
+# ------------------------------------------------------------------ head statistics / fusion
+
+def test_fusion_golden_worked_example(golden_dir):
+    tab = _load_table(os.path.join(golden_dir, "fusion_worked_example.txt"))
+    ck = np.array([0.2, 0.6]).reshape(1, 2, 1)
+    cv = np.array([0.5, 0.7]).reshape(1, 2, 1)
+    for mode, alpha, s in tab:
+        S, st = oracle.fuse(ck, cv, int(mode), return_stats=True)
+        assert abs(st[0, 0, 4] - alpha) < 1e-9
+        assert abs(S[0, 0] - s) < 1e-9
+        np.testing.assert_allclose(st[0, 0, :4], [0.4, 0.6, 0.04, 0.01], rtol=0, atol=1e-15)
+
+
+def test_fusion_stats_vs_numpy_and_properties():
+    rng = np.random.default_rng(7)
+    ck = rng.uniform(-1, 1, (3, 6, 50))
+    cv = rng.uniform(-1, 1, (3, 6, 50))
+    S0, st = oracle.fuse(ck, cv, oracle.FUSE_EQ2, return_stats=True)
+    S1, st1 = oracle.fuse(ck, cv, oracle.FUSE_INVVAR, return_stats=True)
+    np.testing.assert_allclose(st[..., 0], ck.mean(1), atol=1e-15)
+    np.testing.assert_allclose(st[..., 1], cv.mean(1), atol=1e-15)
+    np.testing.assert_allclose(st[..., 2], ck.var(1), atol=1e-15)        # ddof = 0
+    np.testing.assert_allclose(st[..., 3], cv.var(1), atol=1e-15)
+    np.testing.assert_allclose(st[..., 4] + st1[..., 4], 1.0, atol=1e-12)  # the two readings mirror
+    # alpha depends only on the variance ratio, so ddof cannot matter
+    a_ddof1 = ck.var(1, ddof=1) / (ck.var(1, ddof=1) + cv.var(1, ddof=1))
+    np.testing.assert_allclose(st[..., 4], a_ddof1, atol=1e-9)
+    # printed formula: the higher-variance side gets the larger weight
+    hi_k = st[..., 2] > st[..., 3]
+    assert np.all(st[..., 4][hi_k] > 0.5) and np.all(st1[..., 4][hi_k] < 0.5)
+    lo, hi = np.minimum(st[..., 0], st[..., 1]), np.maximum(st[..., 0], st[..., 1])
+    for S in (S0, S1):
+        assert np.all(S >= lo - 1e-15) and np.all(S <= hi + 1e-15)
+    np.testing.assert_allclose(oracle.fuse(ck, cv, oracle.FUSE_KEY_ONLY), ck.mean(1), atol=1e-15)
+    np.testing.assert_allclose(oracle.fuse(ck, cv, oracle.FUSE_VALUE_ONLY), cv.mean(1), atol=1e-15)
+    # head permutation leaves S unchanged
+    perm = rng.permutation(6)
+    np.testing.assert_allclose(oracle.fuse(ck[:, perm], cv[:, perm]), S0, atol=1e-14)
+    # K == V: S = s_k whatever alpha is
+    np.testing.assert_allclose(oracle.fuse(ck, ck), ck.mean(1), atol=1e-15)
+    # equal variances: plain average.  cv = const - ck has the same variance
+    np.testing.assert_allclose(oracle.fuse(ck, 0.25 - ck), np.full((3, 50), 0.125), atol=1e-12)
+
+
+def test_fusion_degenerate_variances():
+    ck = np.full((1, 4, 3), 0.3)
+    cv = np.full((1, 4, 3), 0.9)
+    S, st = oracle.fuse(ck, cv, return_stats=True)          # both variances zero: alpha = 1/2
+    np.testing.assert_allclose(st[..., 4], 0.5, atol=1e-12)
+    np.testing.assert_allclose(S, 0.6, atol=1e-12)
+    one = np.array([0.1]).reshape(1, 1, 1)                   # a single head
+    assert abs(oracle.fuse(one, one * 5)[0, 0] - 0.3) < 1e-12
+
+
+def test_gqa_scoring_equals_repeated_heads():
+    _, k, v, _ = synth.make_random_qkv(1, 8, 2, 40, 16, seed=11)
+    S = oracle.fuse(oracle.anchor_cosine(k), oracle.anchor_cosine(v))
+    kr, vr = k.repeat_interleave(4, dim=1), v.repeat_interleave(4, dim=1)
+    Sr = oracle.fuse(oracle.anchor_cosine(kr), oracle.anchor_cosine(vr))
+    np.testing.assert_allclose(S, Sr, rtol=0, atol=1e-13)
+
+
+# ------------------------------------------------------------------ count / selection
+
+def test_keep_count_golden(golden_dir):
+    tab = _load_table(os.path.join(golden_dir, "keep_count_table.txt"))
+    for n, r, m in tab:
+        assert oracle.keep_count(int(n), r) == int(m)
+
+
+def test_keep_count_is_ceil_exact_rational():
+    for n in (1, 2, 3, 10, 127, 512, 4096, 32768):
+        for num in range(0, 100):
+            r = Fraction(num, 100)
+            want = math.ceil((1 - r) * n)
+            assert oracle.keep_count(n, num / 100.0) == want, (n, num)
+
+
+def _brute_select(s32, m, W):
+    n = s32.shape[0]
+    forced = min(W, m)
+    keep = np.zeros(n, dtype=np.uint8)
+    keep[:forced] = 1
+    rest = np.arange(forced, n)
+    order = rest[np.lexsort((rest, s32[rest]))]             # by score, then by index
+    keep[order[:m - forced]] = 1
+    return keep
+
+
+def test_select_vs_brute_force_and_invariants():
+    rng = np.random.default_rng(13)
+    for n, r, W in [(50, 0.5, 1), (64, 0.25, 4), (33, 0.9, 1), (17, 0.0, 1), (40, 0.5, 0),
+                    (12, 0.8, 5)]:
+        S = rng.uniform(-1, 1, (3, n))
+        S[1] = np.round(S[1] * 4) / 4                        # many exact ties
+        keep, idx, tau = oracle.select(S, r, W)
+        m = oracle.keep_count(n, r)
+        s32 = S.astype(np.float32)
+        for b in range(3):
+            assert keep[b].sum() == m
+            np.testing.assert_array_equal(keep[b], _brute_select(s32[b], m, W))
+            np.testing.assert_array_equal(idx[b], np.nonzero(keep[b])[0])
+            assert np.all(np.diff(idx[b]) > 0)
+            forced = min(W, m)
+            kept_nf = [t for t in idx[b] if t >= forced]
+            filt = np.nonzero(keep[b] == 0)[0]
+            if m == n:
+                assert tau[b] == np.inf
+            elif not kept_nf:
+                assert tau[b] == -np.inf
+            else:
+                assert tau[b] == s32[b, kept_nf].max()
+            if len(filt):
+                assert np.all(s32[b, filt] >= tau[b])        # skip iff S >= tau (ties by index)
+
+
+def test_select_tie_break_and_nesting():
+    S = np.array([[0.5, 0.1, 0.1, 0.1, 0.1, 0.9]])
+    keep, idx, tau = oracle.select(S, 0.5, 1)                # m = 3: forced 0, then ties 1, 2
+    np.testing.assert_array_equal(keep[0], [1, 1, 1, 0, 0, 0])
+    assert tau[0] == np.float32(0.1)
+    rng = np.random.default_rng(17)
+    S = rng.uniform(-1, 1, (2, 200))
+    prev = None
+    for r in (0.0, 0.1, 0.25, 0.5, 0.75, 0.9):
+        keep, _, _ = oracle.select(S, r, 1)
+        if prev is not None:
+            assert np.all(keep <= prev)                       # kept sets shrink monotonically
+        prev = keep
+    assert np.all(oracle.select(S, 0.0, 1)[0] == 1)
+
+
+# ------------------------------------------------------------------ attention
+
+def _sdpa(q, k, v, **kw):
+    return torch.nn.functional.scaled_dot_product_attention(q.double(), k.double(), v.double(), **kw)
+
+
+def test_attention_ratio_zero_is_dense_causal_sdpa():
+    q, k, v, _ = synth.make_random_qkv(2, 4, 4, 24, 16, seed=19)
+    idx = np.tile(np.arange(24, dtype=np.int32), (2, 1))
+    O = oracle.attend(q, k, v, idx)
+    ref = _sdpa(q, k, v, is_causal=True).numpy()
+    np.testing.assert_allclose(O, ref, rtol=0, atol=1e-12)
+
+
+def test_attention_gqa_head_map_vs_sdpa():
+    q, k, v, _ = synth.make_random_qkv(1, 6, 2, 20, 8, seed=23)
+    idx = np.arange(20, dtype=np.int32)[None]
+    O = oracle.attend(q, k, v, idx)
+    ref = _sdpa(q, k.repeat_interleave(3, 1), v.repeat_interleave(3, 1), is_causal=True).numpy()
+    np.testing.assert_allclose(O, ref, rtol=0, atol=1e-12)
+
+
+def test_filtered_attention_equals_compacted_dense_and_masked_dense():
+    q, k, v, _ = synth.make_random_qkv(2, 4, 2, 30, 8, seed=29)
+    res = oracle.filtered_attention(q, k, v, 0.4, warmup=1)
+    O, idx, keep = res["O"], res["kept_idx"], res["keep"]
+    n = 30
+    for b in range(2):
+        ii = torch.from_numpy(idx[b].astype(np.int64))
+        kr, vr = k.repeat_interleave(2, 1), v.repeat_interleave(2, 1)
+        # (i) dense causal attention on the physically compacted tensors
+        ref = _sdpa(q[b:b + 1, :, ii], kr[b:b + 1, :, ii], vr[b:b + 1, :, ii], is_causal=True)[0].numpy()
+        np.testing.assert_allclose(O[b][:, idx[b]], ref, rtol=0, atol=1e-12)
+        # (ii) dense attention with filtered key columns masked out
+        mask = torch.tril(torch.ones(n, n, dtype=torch.bool)) & torch.from_numpy(keep[b].astype(bool))[None, :]
+        mask[:, 0] |= ~mask.any(1)                            # keep fully-masked rows finite
+        ref2 = _sdpa(q[b:b + 1], kr[b:b + 1], vr[b:b + 1], attn_mask=mask)[0].numpy()
+        np.testing.assert_allclose(O[b][:, idx[b]], ref2[:, idx[b]], rtol=0, atol=1e-12)
+        filt = np.nonzero(keep[b] == 0)[0]
+        assert len(filt) and np.all(O[b][:, filt] == 0.0)     # filtered rows exactly zero
+        # first kept row attends only itself: output is its own V row
+        np.testing.assert_allclose(O[b][:, idx[b][0]], vr[b, :, idx[b][0]].double().numpy(), atol=1e-15)
+        # every output row is a convex combination of kept V rows
+        vk = vr[b][:, ii].double().numpy()
+        assert np.all(O[b][:, idx[b]] <= vk.max(1, keepdims=True) + 1e-12)
+        assert np.all(O[b][:, idx[b]] >= vk.min(1, keepdims=True) - 1e-12)
+
+
+def test_attention_softmax_scale_and_rows_entry():
+    q, k, v, _ = synth.make_random_qkv(1, 2, 2, 16, 8, seed=31)
+    idx = np.array([[0, 2, 3, 7, 8, 12, 15]], dtype=np.int32)
+    O = oracle.attend(q, k, v, idx, scale=0.7)
+    ii = torch.from_numpy(idx[0].astype(np.int64))
+    ref = _sdpa(q[:, :, ii], k[:, :, ii], v[:, :, ii], is_causal=True, scale=0.7)[0].numpy()
+    np.testing.assert_allclose(O[0][:, idx[0]], ref, rtol=0, atol=1e-12)
+    rows = np.array([[0, 0, 0], [0, 1, 6], [0, 0, 3]], dtype=np.int32)
+    got = oracle.attend_rows(q, k, v, idx, rows, scale=0.7)
+    for r, (b, h, i) in enumerate(rows):
+        np.testing.assert_array_equal(got[r], O[b, h, idx[b, i]])
+
+
+def test_uniform_attention_closed_form():
+    # all-zero queries: softmax is uniform, so row i is the running mean of the kept V rows
+    q, k, v, _ = synth.make_random_qkv(1, 1, 1, 12, 4, seed=37)
+    idx = np.array([[1, 4, 5, 9]], dtype=np.int32)
+    O = oracle.attend(torch.zeros_like(q), k, v, idx)
+    vk = v[0, 0, idx[0].astype(np.int64)].double().numpy()
+    for i in range(4):
+        np.testing.assert_allclose(O[0, 0, idx[0, i]], vk[:i + 1].mean(0), atol=1e-15)
+
+
+# ------------------------------------------------------------------ whole path on workload 1
+
+def test_whole_path_on_first_workload():
+    w = synth.workload(0)
+    q, k, v, z = synth.make_qkv(w)
+    res = oracle.filtered_attention(q, k, v, 0.5, with_attention=False)
+    m = oracle.keep_count(w.seq, 0.5)
+    assert m == math.ceil(0.5 * w.seq) == res["kept_idx"].shape[1]
+    assert res["keep"].sum() == m * w.batch
+    assert res["keep"][0, 0] == 1                             # warm-up token
+    assert np.all(np.abs(res["fused"]) <= 1.0)
+    # the recipe's point: a token whose identity was seen often scores higher (is more
+    # redundant) on average than one seen for the first time
+    S = res["fused"][0]
+    zz = z[0].numpy()
+    first = np.zeros(w.seq, dtype=bool)
+    seen = set()
+    for t, i in enumerate(zz):
+        first[t] = i not in seen
+        seen.add(i)
+    assert S[~first][10:].mean() > S[first][1:].mean()
