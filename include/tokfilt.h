@@ -1,0 +1,152 @@
+/*
+ * tokfilt.h - C ABI of the MI355X (gfx950) Token Filtering hot path.
+ *
+ * One attention layer of the method of arxiv 2512.07090 ("Leveraging KV Similarity for Online
+ * Structured Pruning in LLMs"): every token is scored by the per-head cosine similarity of
+ * its key and value with the mean of all previous keys and values (Algorithm 1, Section 3.2),
+ * the two similarities are fused across heads with the variance-aware weight of Eq. 2, the
+ * most redundant tokens are filtered at a target ratio, and causal attention runs over the
+ * kept tokens only, filtered tokens receiving a zero attention output (Section 3.2).
+ *
+ * Conventions for every entry point
+ *   - Pointers named Q, K, V, O, fused, sim_k, sim_v, keep, kept_idx, tau and ws are DEVICE
+ *     pointers on the context's GPU.  `tf_params` and everything else is HOST memory.
+ *   - Layout: Q and O are [batch][n_q_heads][seq][head_dim], K and V are
+ *     [batch][n_kv_heads][seq][head_dim]; head_dim is contiguous; the other three extents
+ *     use the element strides given in tf_params (so [batch][seq][head][dim] storage works).
+ *     Base pointers must be 16-byte aligned and strides multiples of 8 elements.
+ *   - Ownership: the caller owns every buffer, including the workspace; the library
+ *     allocates no device memory in these calls and keeps no pointer after returning.
+ *   - Ordering: work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns without waiting.  Outputs are valid once the
+ *     caller has synchronised the stream.
+ *   - Errors: a tf_status is returned, nothing is thrown.  Argument errors are found on
+ *     the host before anything is enqueued and leave all outputs untouched; tf_last_error
+ *     gives a sentence describing the most recent failure on that context.
+ *   - NaN or infinite inputs: behaviour unspecified.
+ */
+#ifndef TOKFILT_H
+#define TOKFILT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tf_ctx tf_ctx; /* opaque: device id, timing events */
+
+typedef enum {
+    TF_OK = 0,
+    TF_ERR_INVALID_ARG = 1,
+    TF_ERR_UNSUPPORTED = 2,
+    TF_ERR_WORKSPACE_TOO_SMALL = 3,
+    TF_ERR_DEVICE = 4
+} tf_status;
+
+typedef enum { TF_F32 = 0, TF_BF16 = 1 } tf_dtype;
+
+/* How the key and value similarities are combined (Eq. 2 / Algorithm 1).
+ *   TF_FUSE_EQ2     alpha = sigma_v^-2 / (sigma_k^-2 + sigma_v^-2), exactly as printed;
+ *   TF_FUSE_INVVAR  alpha = sigma_k^-2 / (sigma_k^-2 + sigma_v^-2), the weighting the prose
+ *                   describes (more weight on the lower-variance side);
+ *   TF_FUSE_KEY_ONLY / TF_FUSE_VALUE_ONLY  alpha = 1 / alpha = 0 (the ablation of Table 7).
+ * S = alpha * s_k + (1 - alpha) * s_v, where s and sigma^2 are the mean and population
+ * variance over KV heads of one token's cosines; 1e-12 is added to each variance. */
+typedef enum {
+    TF_FUSE_EQ2 = 0,
+    TF_FUSE_INVVAR = 1,
+    TF_FUSE_KEY_ONLY = 2,
+    TF_FUSE_VALUE_ONLY = 3
+} tf_fusion;
+
+typedef struct {
+    int32_t batch;
+    int32_t n_q_heads;
+    int32_t n_kv_heads;    /* n_q_heads % n_kv_heads == 0 (grouped-query attention) */
+    int32_t seq;           /* n >= 1 */
+    int32_t head_dim;      /* only 128 is supported */
+    int32_t dtype;         /* tf_dtype of Q, K, V and O */
+    int64_t q_stride[3];   /* element strides of Q for (batch, head, position) */
+    int64_t kv_stride[3];  /* element strides shared by K and V */
+    int64_t o_stride[3];   /* element strides of O */
+    double prune_ratio;    /* r in [0, 1): fraction of tokens filtered */
+    int32_t warmup;        /* W >= 0: the first min(W, m) tokens are always kept (warm-up
+                              phase of Section 3.2); 1 is the usual value, token 0 has no
+                              anchor */
+    int32_t fusion;        /* tf_fusion */
+    float softmax_scale;   /* 0 means 1 / sqrt(head_dim) */
+    int32_t reserved;      /* must be 0 */
+} tf_params;
+
+/* Stages of the path, the order of tf_stage_timing_read's output. */
+enum { TF_STAGE_SCORE = 0, TF_STAGE_FUSE = 1, TF_STAGE_SELECT = 2, TF_STAGE_COMPACT = 3,
+       TF_STAGE_ATTEND = 4, TF_N_STAGES = 5 };
+
+/* Create a context bound to HIP device `device` (made current for the calling thread inside
+ * each call).  *out is set only on TF_OK.  tf_destroy(NULL) is a no-op. */
+tf_status tf_create(tf_ctx **out, int device);
+void tf_destroy(tf_ctx *ctx);
+
+const char *tf_status_string(tf_status s);
+/* Text of the last error recorded on `ctx` ("" if none).  Owned by the context. */
+const char *tf_last_error(const tf_ctx *ctx);
+
+/* m = seq - floor(r * seq + 1e-6), the number of kept tokens (equals ceil((1 - r) * seq)
+ * for ratios with a short decimal expansion).  Returns -1 for seq < 1 or r outside [0, 1). */
+int32_t tf_keep_count(int32_t seq, double prune_ratio);
+
+/* Bytes of workspace any of the calls below needs for `p` (0 if p is invalid). */
+size_t tf_workspace_bytes(const tf_params *p);
+
+/* Scoring (Algorithm 1 anchor / cosine / mean / var / alpha / s_KV lines; Eq. 2).
+ * For each batch row b and position t: per KV head, the cosine of K[b,h,t] with the mean of
+ * K[b,h,0..t-1] (0 for t = 0; denominator max(|a||x|, 1e-8); clamped to [-1, 1]), the same
+ * for V, then the fusion selected by p->fusion.
+ *   fused  out [batch][seq] float                      required
+ *   sim_k  out [batch][n_kv_heads][seq] float          optional (NULL: kept in ws only)
+ *   sim_v  out, same shape                             optional */
+tf_status tf_score(tf_ctx *ctx, const tf_params *p, const void *K, const void *V, float *fused,
+                   float *sim_k, float *sim_v, void *ws, size_t ws_bytes, void *stream);
+
+/* Decision (Algorithm 1 "skip if s_KV > tau", taken at an exact count) and compaction.
+ * Per batch row: with m = tf_keep_count(seq, r), tokens 0..min(W, m)-1 are kept, then the
+ * m - min(W, m) other tokens with the lowest fused score, equal scores in index order.
+ *   fused     in  [batch][seq] float
+ *   keep      out [batch][seq] uint8, 1 = kept
+ *   kept_idx  out [batch][m] int32, kept positions ascending
+ *   tau       out [batch] float: largest score among kept non-forced tokens (+inf when
+ *             nothing is filtered, -inf when no non-forced token is kept).  Optional. */
+tf_status tf_select(tf_ctx *ctx, const tf_params *p, const float *fused, uint8_t *keep,
+                    int32_t *kept_idx, float *tau, void *ws, size_t ws_bytes, void *stream);
+
+/* Causal softmax attention restricted to a kept set (Section 3.2: a skipped token's
+ * attention output is zero; the others attend as usual, here to kept tokens only).
+ * kept_idx: [batch][m] strictly ascending positions in [0, seq), 1 <= m <= seq; the caller
+ * guarantees this, the contents are not checked.  For query
+ * head hq the KV head is hq / (n_q_heads / n_kv_heads).  O rows at positions not listed
+ * are set to zero.  Arithmetic: fp32 throughout for TF_F32; bf16 MFMA with fp32
+ * accumulation and fp32 softmax for TF_BF16. */
+tf_status tf_attend(tf_ctx *ctx, const tf_params *p, const void *Q, const void *K,
+                    const void *V, const int32_t *kept_idx, int32_t m, void *O, void *ws,
+                    size_t ws_bytes, void *stream);
+
+/* The whole path: tf_score -> tf_select -> tf_attend on one stream, no host round trip.
+ * Outputs as in the three calls above; tau may be NULL. */
+tf_status tf_filtered_attention(tf_ctx *ctx, const tf_params *p, const void *Q, const void *K,
+                                const void *V, uint8_t *keep, int32_t *kept_idx, float *fused,
+                                float *tau, void *O, void *ws, size_t ws_bytes, void *stream);
+
+/* Per-stage device timing for measurement.  While enabled, every tf_filtered_attention call
+ * brackets its stages with events on the caller's stream (at most 256 calls are recorded
+ * between reads).  tf_stage_timing_read waits for those events, writes the summed
+ * milliseconds per stage to ms[TF_N_STAGES] and the number of recorded calls to *n_calls,
+ * and clears the record.  Enabling costs a few event records per call. */
+tf_status tf_stage_timing_enable(tf_ctx *ctx, int on);
+tf_status tf_stage_timing_read(tf_ctx *ctx, float *ms, int32_t *n_calls);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TOKFILT_H */

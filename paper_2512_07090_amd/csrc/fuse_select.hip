@@ -1,0 +1,245 @@
+// Head statistics and variance-aware fusion (Algorithm 1 mean/var/alpha/s_KV lines; Eq. 2),
+// the exact-count keep decision (Algorithm 1 "skip if s_KV > tau" with tau placed so that
+// exactly m tokens stay), and stream compaction of the kept positions.
+#include "tf_kernels.h"
+
+namespace tf {
+
+namespace {
+
+// ------------------------------------------------------------------------------ fusion
+// One thread per token; the token's per-head cosines are staged in LDS ([head][token] so that
+// both the global reads and the LDS accesses are unit-stride across the wave) because the
+// variance is taken in two passes and the head count is a run-time value.
+constexpr int kFuseTokens = 64;
+
+__global__ __launch_bounds__(kFuseTokens) void fuse_kernel(const float* __restrict__ sim_k,
+                                                           const float* __restrict__ sim_v,
+                                                           int H, int n, int mode,
+                                                           float* __restrict__ fused)
+{
+    extern __shared__ float stage[];  // [2][H][kFuseTokens]
+    float* ck = stage;
+    float* cv = stage + (size_t)H * kFuseTokens;
+    const int b = blockIdx.y;
+    const int t = blockIdx.x * kFuseTokens + threadIdx.x;
+    if (t >= n) return;
+    const float* pk = sim_k + (long long)b * H * n + t;
+    const float* pv = sim_v + (long long)b * H * n + t;
+    float sk = 0.f, sv = 0.f;
+    for (int h = 0; h < H; ++h) {
+        const float a = pk[(long long)h * n], c = pv[(long long)h * n];
+        ck[h * kFuseTokens + threadIdx.x] = a;
+        cv[h * kFuseTokens + threadIdx.x] = c;
+        sk += a;
+        sv += c;
+    }
+    const float inv_h = 1.0f / (float)H;
+    sk *= inv_h;
+    sv *= inv_h;
+    float vk = 0.f, vv = 0.f;
+    for (int h = 0; h < H; ++h) {
+        const float dk = ck[h * kFuseTokens + threadIdx.x] - sk;
+        const float dv = cv[h * kFuseTokens + threadIdx.x] - sv;
+        vk = fmaf(dk, dk, vk);
+        vv = fmaf(dv, dv, vv);
+    }
+    const float ek = vk * inv_h + 1e-12f, ev = vv * inv_h + 1e-12f;
+    float alpha;
+    if (mode == 0)
+        alpha = ek / (ek + ev);  // = (1/ev) / (1/ek + 1/ev), the printed form of Eq. 2
+    else if (mode == 1)
+        alpha = ev / (ek + ev);  // = (1/ek) / (1/ek + 1/ev)
+    else
+        alpha = mode == 2 ? 1.f : 0.f;
+    fused[(long long)b * n + t] = alpha * sk + (1.f - alpha) * sv;
+}
+
+// ------------------------------------------------------------------------------ block scan
+constexpr int kSelThreads = 1024;
+constexpr int kSelWaves = kSelThreads / 64;
+
+// Exclusive prefix sum of one int per thread over the 1024-thread block; *total gets the
+// block sum.  `lds` must hold kSelWaves + 1 ints.  Ends with a barrier, so `lds` may be
+// reused immediately.
+__device__ __forceinline__ int block_excl_scan(int v, int* lds, int* total)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int o = __shfl_up(inc, off);
+        if (lane >= off) inc += o;
+    }
+    if (lane == 63) lds[wave] = inc;
+    __syncthreads();
+    int base = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < kSelWaves; ++w) {
+        const int x = lds[w];
+        if (w < wave) base += x;
+        tot += x;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + inc - v;
+}
+
+// Order-preserving map from float to unsigned; -0 is folded onto +0 so that the two compare
+// equal, as they do as floats (ties then go by index).
+__device__ __forceinline__ unsigned f2key(float f)
+{
+    unsigned u = __builtin_bit_cast(unsigned, f);
+    if (u == 0x80000000u) u = 0u;
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float key2f(unsigned k)
+{
+    const unsigned u = (k & 0x80000000u) ? (k & 0x7fffffffu) : ~k;
+    return __builtin_bit_cast(float, u);
+}
+
+// ------------------------------------------------------------------------------ decision
+// One workgroup per batch row.  The `want`-th smallest score among the non-forced tokens is
+// found by a most-significant-digit-first radix select on the order-preserving keys (four
+// passes of 8 bits, a 256-bin LDS histogram each); tokens strictly below it are kept, tokens
+// equal to it are kept in index order until the count is met.
+__global__ __launch_bounds__(kSelThreads) void select_kernel(const float* __restrict__ fused,
+                                                             int n, int m, int warmup,
+                                                             uint8_t* __restrict__ keep,
+                                                             float* __restrict__ tau)
+{
+    __shared__ int hist[256];
+    __shared__ int scan_lds[kSelWaves + 1];
+    __shared__ unsigned sel_prefix;
+    __shared__ int sel_k;
+
+    const int b = blockIdx.x;
+    const float* S = fused + (long long)b * n;
+    uint8_t* kp = keep + (long long)b * n;
+    const int tid = threadIdx.x;
+    const int forced = min(max(warmup, 0), m);
+    const int want = m - forced;
+
+    if (m >= n || want <= 0) {
+        for (int t = tid; t < n; t += kSelThreads) kp[t] = (m >= n || t < forced) ? 1 : 0;
+        if (tid == 0 && tau) tau[b] = m >= n ? INFINITY : -INFINITY;
+        return;
+    }
+
+    unsigned prefix = 0;
+    int k = want;  // 1-based rank still to find inside the current prefix bucket
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        const unsigned himask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int t = forced + tid; t < n; t += kSelThreads) {
+            const unsigned key = f2key(S[t]);
+            if ((key & himask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+        }
+        __syncthreads();
+        const int cnt = tid < 256 ? hist[tid] : 0;
+        int total;
+        const int before = block_excl_scan(cnt, scan_lds, &total);
+        if (tid < 256 && before < k && k <= before + cnt) {
+            sel_prefix = prefix | ((unsigned)tid << shift);
+            sel_k = k - before;
+        }
+        __syncthreads();
+        prefix = sel_prefix;
+        k = sel_k;
+        __syncthreads();
+    }
+    const unsigned tkey = prefix;  // key of the want-th smallest score
+    const int k_eq = k;            // how many tokens equal to it are kept (>= 1)
+    if (tid == 0 && tau) tau[b] = key2f(tkey);
+
+    int eq_base = 0;
+    for (int t0 = forced; t0 < n; t0 += kSelThreads) {
+        const int t = t0 + tid;
+        unsigned key = 0xffffffffu;
+        if (t < n) key = f2key(S[t]);
+        const int is_eq = (t < n && key == tkey) ? 1 : 0;
+        int total;
+        const int rank = eq_base + block_excl_scan(is_eq, scan_lds, &total);
+        eq_base += total;
+        if (t < n) kp[t] = (key < tkey || (is_eq && rank < k_eq)) ? 1 : 0;
+    }
+    for (int t = tid; t < forced; t += kSelThreads) kp[t] = 1;
+}
+
+// ------------------------------------------------------------------------------ compaction
+// One workgroup per batch row: ordered exclusive prefix count of the keep flags, kept
+// positions written ascending.
+__global__ __launch_bounds__(kSelThreads) void compact_kernel(const uint8_t* __restrict__ keep,
+                                                              int n, int m,
+                                                              int32_t* __restrict__ kept_idx)
+{
+    __shared__ int scan_lds[kSelWaves + 1];
+    const int b = blockIdx.x;
+    const uint8_t* kp = keep + (long long)b * n;
+    int32_t* out = kept_idx + (long long)b * m;
+    int base = 0;
+    for (int t0 = 0; t0 < n; t0 += kSelThreads) {
+        const int t = t0 + threadIdx.x;
+        const int flag = (t < n && kp[t]) ? 1 : 0;
+        int total;
+        const int pos = base + block_excl_scan(flag, scan_lds, &total);
+        base += total;
+        if (flag && pos < m) out[pos] = t;
+    }
+}
+
+__global__ void mask_from_idx_kernel(const int32_t* __restrict__ kept_idx, int n, int m,
+                                     uint8_t* __restrict__ keep)
+{
+    const int b = blockIdx.y;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < m) {
+        const int p = kept_idx[(long long)b * m + i];
+        if (p >= 0 && p < n) keep[(long long)b * n + p] = 1;
+    }
+}
+
+__global__ void clear_bytes_kernel(uint8_t* p, long long count)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) p[i] = 0;
+}
+
+}  // namespace
+
+hipError_t launch_fuse(const Dims& d, int fusion, const float* sim_k, const float* sim_v,
+                       float* fused, hipStream_t s)
+{
+    const size_t lds = (size_t)2 * d.Hkv * kFuseTokens * sizeof(float);
+    dim3 grid((d.n + kFuseTokens - 1) / kFuseTokens, d.B);
+    fuse_kernel<<<grid, dim3(kFuseTokens), lds, s>>>(sim_k, sim_v, d.Hkv, d.n, fusion, fused);
+    return hipGetLastError();
+}
+
+hipError_t launch_select(const Dims& d, int warmup, const float* fused, uint8_t* keep,
+                         float* tau, hipStream_t s)
+{
+    select_kernel<<<dim3(d.B), dim3(kSelThreads), 0, s>>>(fused, d.n, d.m, warmup, keep, tau);
+    return hipGetLastError();
+}
+
+hipError_t launch_compact(const Dims& d, const uint8_t* keep, int32_t* kept_idx, hipStream_t s)
+{
+    compact_kernel<<<dim3(d.B), dim3(kSelThreads), 0, s>>>(keep, d.n, d.m, kept_idx);
+    return hipGetLastError();
+}
+
+hipError_t launch_mask_from_idx(const Dims& d, const int32_t* kept_idx, uint8_t* keep,
+                                hipStream_t s)
+{
+    const long long count = (long long)d.B * d.n;
+    clear_bytes_kernel<<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s>>>(keep, count);
+    mask_from_idx_kernel<<<dim3((d.m + 255) / 256, d.B), dim3(256), 0, s>>>(kept_idx, d.n, d.m,
+                                                                           keep);
+    return hipGetLastError();
+}
+
+}  // namespace tf

@@ -1,0 +1,289 @@
+// Scoring stage: exclusive prefix sums of K and V along the sequence and, fused with them, the
+// per-head cosine of every row with the sum of the rows before it (Algorithm 1, anchor and
+// cosine lines; Section 3.2).  cos(mean, x) = cos(sum, x), so the running SUM is carried and
+// the 1/t only enters the guard on the denominator.
+//
+// Work decomposition.  A chain is one (tensor, batch row, KV head): n rows of 128 elements,
+// contiguous per row.  A chain is cut into `nseg` segments; one workgroup of 256 threads
+// walks one segment in tiles of 128 rows and reads every element exactly once.
+//   thread = (row group rg = tid / 16, column slice l = tid % 16); a thread owns 8
+//   consecutive rows of the tile and 8 consecutive columns, so a 16-lane DPP row reads one
+//   full 256-byte (bf16) row per load and the three 128-long reductions of a row finish
+//   inside that DPP row.
+//   Per tile: (1) per-thread column totals of its 8 rows; (2) exclusive scan of those totals
+//   over the 16 row groups (bpermute inside a wave, 2 KB of LDS across the 4 waves);
+//   (3) each thread replays its 8 rows against its running prefix.
+// With nseg > 1 a first kernel reduces every segment but the last to its column totals and
+// the scan kernel starts from the sum of the totals before it.
+#include "tf_kernels.h"
+
+namespace tf {
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int kR = 8;               // rows per thread per tile
+constexpr int kTile = 16 * kR;      // rows per tile
+
+template <typename T>
+struct Row8;
+
+template <>
+struct Row8<uint16_t> {             // bf16 storage
+    uint4 raw;
+    __device__ __forceinline__ void load(const uint16_t* p) { raw = *reinterpret_cast<const uint4*>(p); }
+    __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
+    __device__ __forceinline__ void unpack(float* x) const
+    {
+        const unsigned w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            x[2 * i] = __builtin_bit_cast(float, w[i] << 16);
+            x[2 * i + 1] = __builtin_bit_cast(float, w[i] & 0xffff0000u);
+        }
+    }
+};
+
+template <>
+struct Row8<float> {
+    float4 lo, hi;
+    __device__ __forceinline__ void load(const float* p)
+    {
+        lo = *reinterpret_cast<const float4*>(p);
+        hi = *reinterpret_cast<const float4*>(p + 4);
+    }
+    __device__ __forceinline__ void zero() { lo = hi = make_float4(0.f, 0.f, 0.f, 0.f); }
+    __device__ __forceinline__ void unpack(float* x) const
+    {
+        x[0] = lo.x; x[1] = lo.y; x[2] = lo.z; x[3] = lo.w;
+        x[4] = hi.x; x[5] = hi.y; x[6] = hi.z; x[7] = hi.w;
+    }
+};
+
+template <typename T>
+__device__ __forceinline__ void load_tile(Row8<T>* rows, const T* X, long long s_t, int t_first,
+                                          int t_end, int col)
+{
+#pragma unroll
+    for (int r = 0; r < kR; ++r) {
+        const int t = t_first + r;
+        if (t < t_end)
+            rows[r].load(X + (long long)t * s_t + col);
+        else
+            rows[r].zero();
+    }
+}
+
+// Column totals of segments 0..nseg-2 of every chain.
+template <typename T>
+__global__ __launch_bounds__(kThreads) void segment_totals_kernel(
+    const T* __restrict__ K, const T* __restrict__ V, long long s_b, long long s_h, long long s_t,
+    int BH, int Hkv, int n, int nseg, int seg_len, float* __restrict__ seg_tot)
+{
+    __shared__ float part[16][kHeadDim];
+    const int seg = blockIdx.x % (nseg - 1);
+    const int chain = blockIdx.x / (nseg - 1);
+    const int tensor = chain / BH, bh = chain % BH;
+    const T* X = (tensor ? V : K) + (long long)(bh / Hkv) * s_b + (long long)(bh % Hkv) * s_h;
+    const int l = threadIdx.x & 15, rg = threadIdx.x >> 4;
+    const int t_begin = seg * seg_len;
+    const int t_end = min(n, t_begin + seg_len);
+    float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int t0 = t_begin; t0 < t_end; t0 += kTile) {
+        Row8<T> rows[kR];
+        load_tile(rows, X, s_t, t0 + rg * kR, t_end, 8 * l);
+#pragma unroll
+        for (int r = 0; r < kR; ++r) {
+            float x[8];
+            rows[r].unpack(x);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[c] += x[c];
+        }
+    }
+#pragma unroll
+    for (int c = 0; c < 8; ++c) part[rg][8 * l + c] = acc[c];
+    __syncthreads();
+    if (threadIdx.x < kHeadDim) {
+        float s = 0.f;
+#pragma unroll
+        for (int g = 0; g < 16; ++g) s += part[g][threadIdx.x];
+        seg_tot[((long long)chain * nseg + seg) * kHeadDim + threadIdx.x] = s;
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(kThreads) void scan_score_kernel(
+    const T* __restrict__ K, const T* __restrict__ V, long long s_b, long long s_h, long long s_t,
+    int BH, int Hkv, int n, int nseg, int seg_len, const float* __restrict__ seg_tot,
+    float* __restrict__ sim_k, float* __restrict__ sim_v)
+{
+    __shared__ float wtot[2][4][kHeadDim];
+
+    const int seg = blockIdx.x % nseg;
+    const int chain = blockIdx.x / nseg;
+    const int tensor = chain / BH, bh = chain % BH;
+    const T* X = (tensor ? V : K) + (long long)(bh / Hkv) * s_b + (long long)(bh % Hkv) * s_h;
+    float* sim = (tensor ? sim_v : sim_k) + (long long)bh * n;
+
+    const int tid = threadIdx.x;
+    const int l = tid & 15;          // column slice: columns 8l .. 8l+7
+    const int rg = tid >> 4;         // row group in the tile: rows 8rg .. 8rg+7
+    const int wave = tid >> 6;
+    const int rgw = (tid >> 4) & 3;  // row group inside the wave
+
+    const int t_begin = seg * seg_len;
+    const int t_end = min(n, t_begin + seg_len);
+
+    float carry[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) carry[c] = 0.f;
+    for (int s = 0; s < seg; ++s) {
+        const float* p = seg_tot + ((long long)chain * nseg + s) * kHeadDim + 8 * l;
+        const float4 a = *reinterpret_cast<const float4*>(p);
+        const float4 b = *reinterpret_cast<const float4*>(p + 4);
+        carry[0] += a.x; carry[1] += a.y; carry[2] += a.z; carry[3] += a.w;
+        carry[4] += b.x; carry[5] += b.y; carry[6] += b.z; carry[7] += b.w;
+    }
+
+    Row8<T> buf0[kR], buf1[kR];
+    load_tile(buf0, X, s_t, t_begin + rg * kR, t_end, 8 * l);
+
+    int parity = 0;
+    auto process = [&](const Row8<T>* rows, int t0) {
+        float x[kR][8];
+        float tot[8];
+#pragma unroll
+        for (int r = 0; r < kR; ++r) rows[r].unpack(x[r]);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            float s = x[0][c];
+#pragma unroll
+            for (int r = 1; r < kR; ++r) s += x[r][c];
+            tot[c] = s;
+        }
+        // exclusive scan of the row-group totals inside the wave (4 row groups of 16 lanes)
+        float excl[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            float a = __shfl_up(tot[c], 16);
+            a = rgw >= 1 ? a : 0.f;
+            const float pair = tot[c] + a;
+            float b = __shfl_up(pair, 32);
+            b = rgw >= 2 ? b : 0.f;
+            excl[c] = a + b;
+        }
+        if (rgw == 3) {
+            float4* dst = reinterpret_cast<float4*>(&wtot[parity][wave][8 * l]);
+            dst[0] = make_float4(excl[0] + tot[0], excl[1] + tot[1], excl[2] + tot[2], excl[3] + tot[3]);
+            dst[1] = make_float4(excl[4] + tot[4], excl[5] + tot[5], excl[6] + tot[6], excl[7] + tot[7]);
+        }
+        __syncthreads();
+        float A[8], all[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) { A[c] = carry[c]; all[c] = 0.f; }
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float4* src = reinterpret_cast<const float4*>(&wtot[parity][w][8 * l]);
+            const float4 a = src[0], b = src[1];
+            const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                all[c] += v[c];
+                if (w < wave) A[c] += v[c];
+            }
+        }
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            carry[c] += all[c];
+            A[c] += excl[c];
+        }
+        parity ^= 1;
+
+        // replay the 8 rows against the running prefix; lane r of the DPP row keeps row r
+        float my_dot = 0.f, my_aa = 0.f, my_xx = 0.f;
+#pragma unroll
+        for (int r = 0; r < kR; ++r) {
+            float dot = 0.f, aa = 0.f, xx = 0.f;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                dot = fmaf(A[c], x[r][c], dot);
+                aa = fmaf(A[c], A[c], aa);
+                xx = fmaf(x[r][c], x[r][c], xx);
+                A[c] += x[r][c];
+            }
+            dot = row16_sum(dot);
+            aa = row16_sum(aa);
+            xx = row16_sum(xx);
+            if (l == r) { my_dot = dot; my_aa = aa; my_xx = xx; }
+        }
+        if (l < kR) {
+            const int t = t0 + rg * kR + l;
+            if (t < t_end) {
+                // cosine of row t with the MEAN of rows 0..t-1: numerator and denominator
+                // both carry the 1/t so that the 1e-8 floor applies to |mean| * |x|
+                const float inv_t = t > 0 ? 1.0f / (float)t : 0.f;
+                const float den = fmaxf(sqrtf(my_aa) * sqrtf(my_xx) * inv_t, 1e-8f);
+                float cs = (my_dot * inv_t) / den;
+                cs = fminf(1.f, fmaxf(-1.f, cs));
+                sim[t] = cs;
+            }
+        }
+    };
+
+    for (int t0 = t_begin; t0 < t_end; t0 += 2 * kTile) {
+        const bool more1 = t0 + kTile < t_end;
+        if (more1) load_tile(buf1, X, s_t, t0 + kTile + rg * kR, t_end, 8 * l);
+        process(buf0, t0);
+        if (!more1) break;
+        if (t0 + 2 * kTile < t_end) load_tile(buf0, X, s_t, t0 + 2 * kTile + rg * kR, t_end, 8 * l);
+        process(buf1, t0 + kTile);
+    }
+}
+
+}  // namespace
+
+ScorePlan plan_score(int B, int Hkv, int n)
+{
+    const int chains = 2 * B * Hkv;
+    const int tiles = (n + kTile - 1) / kTile;
+    int want = chains >= 256 ? 1 : (512 + chains - 1) / chains;
+    int nseg = want < tiles ? want : tiles;
+    if (nseg < 1) nseg = 1;
+    const int tiles_per_seg = (tiles + nseg - 1) / nseg;
+    nseg = (tiles + tiles_per_seg - 1) / tiles_per_seg;
+    return ScorePlan{nseg, tiles_per_seg * kTile};
+}
+
+size_t score_scratch_floats(const Dims& d)
+{
+    const ScorePlan p = plan_score(d.B, d.Hkv, d.n);
+    return (size_t)2 * d.B * d.Hkv * p.nseg * kHeadDim;
+}
+
+template <typename T>
+static hipError_t launch_score_t(const Dims& d, const T* K, const T* V, float* sim_k,
+                                 float* sim_v, float* seg_tot, hipStream_t s)
+{
+    const ScorePlan p = plan_score(d.B, d.Hkv, d.n);
+    const int BH = d.B * d.Hkv;
+    const int chains = 2 * BH;
+    if (p.nseg > 1) {
+        segment_totals_kernel<T><<<dim3(chains * (p.nseg - 1)), dim3(kThreads), 0, s>>>(
+            K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot);
+    }
+    scan_score_kernel<T><<<dim3(chains * p.nseg), dim3(kThreads), 0, s>>>(
+        K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k,
+        sim_v);
+    return hipGetLastError();
+}
+
+hipError_t launch_score(const Dims& d, int dtype, const void* K, const void* V, float* sim_k,
+                        float* sim_v, float* seg_tot, hipStream_t s)
+{
+    if (dtype == 0)
+        return launch_score_t<float>(d, (const float*)K, (const float*)V, sim_k, sim_v, seg_tot, s);
+    return launch_score_t<uint16_t>(d, (const uint16_t*)K, (const uint16_t*)V, sim_k, sim_v,
+                                    seg_tot, s);
+}
+
+}  // namespace tf

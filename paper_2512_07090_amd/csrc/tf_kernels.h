@@ -1,0 +1,72 @@
+// Internal declarations shared by the HIP sources of the token-filter library (gfx950 only).
+// Host launchers are declared here and defined next to their kernels; tokfilt_api.hip
+// validates arguments and sequences them.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace tf {
+
+constexpr int kHeadDim = 128;
+
+// Problem extents and element strides, passed by value to kernels.
+struct Dims {
+    int B, Hq, Hkv, n, m;
+    long long qs[3];   // Q strides for (batch, head, position)
+    long long kvs[3];  // K / V strides
+    long long os[3];   // O strides
+};
+
+// ---- scoring: exclusive prefix sums of K and V along the sequence + per-head cosines -----
+struct ScorePlan {
+    int nseg;     // sequence segments per (tensor, batch, head) chain
+    int seg_len;  // tokens per segment, a multiple of the scan tile
+};
+ScorePlan plan_score(int B, int Hkv, int n);
+size_t score_scratch_floats(const Dims& d);  // segment totals
+// sim_k / sim_v: [B][Hkv][n] float.  seg_tot: scratch of score_scratch_floats() floats.
+hipError_t launch_score(const Dims& d, int dtype, const void* K, const void* V, float* sim_k,
+                        float* sim_v, float* seg_tot, hipStream_t s);
+
+// ---- head statistics + variance-aware fusion ----------------------------------------------
+hipError_t launch_fuse(const Dims& d, int fusion, const float* sim_k, const float* sim_v,
+                       float* fused, hipStream_t s);
+
+// ---- exact-count decision and stream compaction -------------------------------------------
+hipError_t launch_select(const Dims& d, int warmup, const float* fused, uint8_t* keep,
+                         float* tau, hipStream_t s);
+hipError_t launch_compact(const Dims& d, const uint8_t* keep, int32_t* kept_idx, hipStream_t s);
+// keep mask from an index list (for callers that bring their own kept set)
+hipError_t launch_mask_from_idx(const Dims& d, const int32_t* kept_idx, uint8_t* keep,
+                                hipStream_t s);
+
+// ---- attention over the kept tokens -------------------------------------------------------
+hipError_t launch_zero_filtered(const Dims& d, int dtype, const uint8_t* keep, void* O,
+                                hipStream_t s);
+hipError_t launch_attend_f32(const Dims& d, float scale, const float* Q, const float* K,
+                             const float* V, const int32_t* kept_idx, float* O, hipStream_t s);
+hipError_t launch_attend_bf16(const Dims& d, float scale, const void* Q, const void* K,
+                              const void* V, const int32_t* kept_idx, void* O, hipStream_t s);
+
+// ---- small device helpers -----------------------------------------------------------------
+#ifdef __HIPCC__
+template <int CTRL>
+__device__ __forceinline__ float dpp_mov(float v)
+{
+    return __builtin_bit_cast(
+        float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+// Sum over each aligned group of 16 lanes (one DPP row); every lane ends with the total.
+__device__ __forceinline__ float row16_sum(float v)
+{
+    v += dpp_mov<0xB1>(v);   // quad_perm [1,0,3,2]
+    v += dpp_mov<0x4E>(v);   // quad_perm [2,3,0,1]
+    v += dpp_mov<0x141>(v);  // row_half_mirror
+    v += dpp_mov<0x140>(v);  // row_mirror
+    return v;
+}
+#endif
+
+}  // namespace tf

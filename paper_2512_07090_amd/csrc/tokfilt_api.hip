@@ -1,0 +1,324 @@
+// C ABI of the token-filter library: argument checking, workspace carving and the order in
+// which the kernels are enqueued.  All arithmetic of the method lives in the kernels.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "../../include/tokfilt.h"
+#include "tf_kernels.h"
+
+struct tf_ctx {
+    int device;
+    char err[256];
+    int timing_on;
+    int timing_calls;
+    hipEvent_t ev[256][TF_N_STAGES + 1];
+    bool ev_ready;
+};
+
+namespace {
+
+constexpr int kMaxTimedCalls = 256;
+constexpr int kMaxKvHeads = 128;  // LDS staging of the fusion kernel
+
+tf_status fail(tf_ctx* c, tf_status s, const char* fmt, ...) __attribute__((format(printf, 3, 4)));
+tf_status fail(tf_ctx* c, tf_status s, const char* fmt, ...)
+{
+    if (c) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(c->err, sizeof(c->err), fmt, ap);
+        va_end(ap);
+    }
+    return s;
+}
+
+size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct Workspace {
+    size_t sim_k, sim_v, seg_tot, keep_tmp, total;  // byte offsets
+};
+
+// Pure shape validation, usable without a context.
+tf_status check_shape(const tf_params* p, const char** why)
+{
+    *why = "";
+    if (!p) { *why = "params is NULL"; return TF_ERR_INVALID_ARG; }
+    if (p->batch < 1 || p->n_q_heads < 1 || p->n_kv_heads < 1 || p->seq < 1) {
+        *why = "batch, head counts and seq must be >= 1"; return TF_ERR_INVALID_ARG;
+    }
+    if (p->n_q_heads % p->n_kv_heads != 0) {
+        *why = "n_q_heads must be a multiple of n_kv_heads"; return TF_ERR_INVALID_ARG;
+    }
+    if (p->dtype != TF_F32 && p->dtype != TF_BF16) { *why = "unknown dtype"; return TF_ERR_INVALID_ARG; }
+    if (p->fusion < TF_FUSE_EQ2 || p->fusion > TF_FUSE_VALUE_ONLY) {
+        *why = "unknown fusion mode"; return TF_ERR_INVALID_ARG;
+    }
+    if (!(p->prune_ratio >= 0.0 && p->prune_ratio < 1.0)) {
+        *why = "prune_ratio must be in [0, 1)"; return TF_ERR_INVALID_ARG;
+    }
+    if (p->warmup < 0) { *why = "warmup must be >= 0"; return TF_ERR_INVALID_ARG; }
+    if (p->reserved != 0) { *why = "reserved must be 0"; return TF_ERR_INVALID_ARG; }
+    if (!(p->softmax_scale >= 0.f) || isinf(p->softmax_scale)) {
+        *why = "softmax_scale must be finite and >= 0"; return TF_ERR_INVALID_ARG;
+    }
+    const int64_t* st[3] = {p->q_stride, p->kv_stride, p->o_stride};
+    for (int a = 0; a < 3; ++a)
+        for (int i = 0; i < 3; ++i)
+            if (st[a][i] < 0 || st[a][i] % 8 != 0 || (i == 2 && st[a][i] < p->head_dim)) {
+                *why = "strides must be non-negative multiples of 8 elements, position stride >= head_dim";
+                return TF_ERR_INVALID_ARG;
+            }
+    if (p->head_dim != tf::kHeadDim) { *why = "only head_dim 128 is supported"; return TF_ERR_UNSUPPORTED; }
+    if (p->n_kv_heads > kMaxKvHeads) { *why = "more than 128 KV heads is not supported"; return TF_ERR_UNSUPPORTED; }
+    if ((int64_t)p->batch * p->seq > (int64_t)1 << 30) { *why = "batch * seq too large"; return TF_ERR_UNSUPPORTED; }
+    return TF_OK;
+}
+
+tf::Dims make_dims(const tf_params* p, int m)
+{
+    tf::Dims d;
+    d.B = p->batch; d.Hq = p->n_q_heads; d.Hkv = p->n_kv_heads; d.n = p->seq; d.m = m;
+    for (int i = 0; i < 3; ++i) { d.qs[i] = p->q_stride[i]; d.kvs[i] = p->kv_stride[i]; d.os[i] = p->o_stride[i]; }
+    return d;
+}
+
+Workspace carve(const tf_params* p)
+{
+    const tf::Dims d = make_dims(p, 0);
+    Workspace w;
+    const size_t sims = align256((size_t)p->batch * p->n_kv_heads * p->seq * sizeof(float));
+    size_t off = 0;
+    w.sim_k = off; off += sims;
+    w.sim_v = off; off += sims;
+    w.seg_tot = off; off += align256(tf::score_scratch_floats(d) * sizeof(float));
+    w.keep_tmp = off; off += align256((size_t)p->batch * p->seq);
+    w.total = off;
+    return w;
+}
+
+bool misaligned(const void* p) { return ((uintptr_t)p & 15) != 0; }
+
+tf_status enter(tf_ctx* ctx, const tf_params* p, void* ws, size_t ws_bytes, Workspace* w)
+{
+    if (!ctx) return TF_ERR_INVALID_ARG;
+    const char* why;
+    const tf_status s = check_shape(p, &why);
+    if (s != TF_OK) return fail(ctx, s, "%s", why);
+    *w = carve(p);
+    if (!ws) return fail(ctx, TF_ERR_INVALID_ARG, "workspace pointer is NULL");
+    if (misaligned(ws)) return fail(ctx, TF_ERR_INVALID_ARG, "workspace must be 16-byte aligned");
+    if (ws_bytes < w->total)
+        return fail(ctx, TF_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", ws_bytes, w->total);
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, TF_ERR_DEVICE, "hipSetDevice(%d) failed", ctx->device);
+    return TF_OK;
+}
+
+tf_status dev(tf_ctx* ctx, hipError_t e, const char* what)
+{
+    if (e == hipSuccess) return TF_OK;
+    return fail(ctx, TF_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
+}
+
+tf_status run_attend(tf_ctx* ctx, const tf_params* p, const tf::Dims& d, const void* Q,
+                     const void* K, const void* V, const int32_t* kept_idx,
+                     const uint8_t* keep, void* O, hipStream_t s)
+{
+    tf_status st = dev(ctx, tf::launch_zero_filtered(d, p->dtype, keep, O, s), "zero-fill launch");
+    if (st != TF_OK) return st;
+    const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
+    if (p->dtype == TF_F32)
+        return dev(ctx, tf::launch_attend_f32(d, scale, (const float*)Q, (const float*)K, (const float*)V,
+                                              kept_idx, (float*)O, s), "fp32 attention launch");
+    return dev(ctx, tf::launch_attend_bf16(d, scale, Q, K, V, kept_idx, O, s), "bf16 attention launch");
+}
+
+void mark(tf_ctx* ctx, int slot, int stage, hipStream_t s)
+{
+    if (slot >= 0) (void)hipEventRecord(ctx->ev[slot][stage], s);
+}
+
+}  // namespace
+
+extern "C" {
+
+tf_status tf_create(tf_ctx** out, int device)
+{
+    if (!out) return TF_ERR_INVALID_ARG;
+    int count = 0;
+    if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return TF_ERR_DEVICE;
+    tf_ctx* c = new (std::nothrow) tf_ctx;
+    if (!c) return TF_ERR_DEVICE;
+    memset(c, 0, sizeof(*c));
+    c->device = device;
+    *out = c;
+    return TF_OK;
+}
+
+void tf_destroy(tf_ctx* ctx)
+{
+    if (!ctx) return;
+    if (ctx->ev_ready) {
+        (void)hipSetDevice(ctx->device);
+        for (int i = 0; i < kMaxTimedCalls; ++i)
+            for (int j = 0; j <= TF_N_STAGES; ++j) (void)hipEventDestroy(ctx->ev[i][j]);
+    }
+    delete ctx;
+}
+
+const char* tf_status_string(tf_status s)
+{
+    switch (s) {
+        case TF_OK: return "ok";
+        case TF_ERR_INVALID_ARG: return "invalid argument";
+        case TF_ERR_UNSUPPORTED: return "unsupported configuration";
+        case TF_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+        case TF_ERR_DEVICE: return "device error";
+    }
+    return "unknown status";
+}
+
+const char* tf_last_error(const tf_ctx* ctx) { return ctx ? ctx->err : ""; }
+
+int32_t tf_keep_count(int32_t seq, double prune_ratio)
+{
+    if (seq < 1 || !(prune_ratio >= 0.0 && prune_ratio < 1.0)) return -1;
+    return seq - (int32_t)floor(prune_ratio * (double)seq + 1e-6);
+}
+
+size_t tf_workspace_bytes(const tf_params* p)
+{
+    const char* why;
+    if (check_shape(p, &why) != TF_OK) return 0;
+    return carve(p).total;
+}
+
+tf_status tf_score(tf_ctx* ctx, const tf_params* p, const void* K, const void* V, float* fused,
+                   float* sim_k, float* sim_v, void* ws, size_t ws_bytes, void* stream)
+{
+    Workspace w;
+    tf_status st = enter(ctx, p, ws, ws_bytes, &w);
+    if (st != TF_OK) return st;
+    if (!K || !V || !fused) return fail(ctx, TF_ERR_INVALID_ARG, "K, V and fused must not be NULL");
+    if (misaligned(K) || misaligned(V)) return fail(ctx, TF_ERR_INVALID_ARG, "K and V must be 16-byte aligned");
+    const tf::Dims d = make_dims(p, tf_keep_count(p->seq, p->prune_ratio));
+    hipStream_t s = (hipStream_t)stream;
+    char* base = (char*)ws;
+    float* sk = sim_k ? sim_k : (float*)(base + w.sim_k);
+    float* sv = sim_v ? sim_v : (float*)(base + w.sim_v);
+    st = dev(ctx, tf::launch_score(d, p->dtype, K, V, sk, sv, (float*)(base + w.seg_tot), s), "score launch");
+    if (st != TF_OK) return st;
+    return dev(ctx, tf::launch_fuse(d, p->fusion, sk, sv, fused, s), "fuse launch");
+}
+
+tf_status tf_select(tf_ctx* ctx, const tf_params* p, const float* fused, uint8_t* keep,
+                    int32_t* kept_idx, float* tau, void* ws, size_t ws_bytes, void* stream)
+{
+    Workspace w;
+    tf_status st = enter(ctx, p, ws, ws_bytes, &w);
+    if (st != TF_OK) return st;
+    if (!fused || !keep || !kept_idx) return fail(ctx, TF_ERR_INVALID_ARG, "fused, keep and kept_idx must not be NULL");
+    const tf::Dims d = make_dims(p, tf_keep_count(p->seq, p->prune_ratio));
+    hipStream_t s = (hipStream_t)stream;
+    st = dev(ctx, tf::launch_select(d, p->warmup, fused, keep, tau, s), "select launch");
+    if (st != TF_OK) return st;
+    return dev(ctx, tf::launch_compact(d, keep, kept_idx, s), "compact launch");
+}
+
+tf_status tf_attend(tf_ctx* ctx, const tf_params* p, const void* Q, const void* K, const void* V,
+                    const int32_t* kept_idx, int32_t m, void* O, void* ws, size_t ws_bytes,
+                    void* stream)
+{
+    Workspace w;
+    tf_status st = enter(ctx, p, ws, ws_bytes, &w);
+    if (st != TF_OK) return st;
+    if (!Q || !K || !V || !O || !kept_idx) return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V, O and kept_idx must not be NULL");
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O))
+        return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V and O must be 16-byte aligned");
+    if (m < 1 || m > p->seq) return fail(ctx, TF_ERR_INVALID_ARG, "m must be in [1, seq]");
+    const tf::Dims d = make_dims(p, m);
+    hipStream_t s = (hipStream_t)stream;
+    uint8_t* keep = (uint8_t*)((char*)ws + w.keep_tmp);
+    st = dev(ctx, tf::launch_mask_from_idx(d, kept_idx, keep, s), "mask launch");
+    if (st != TF_OK) return st;
+    return run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, s);
+}
+
+tf_status tf_filtered_attention(tf_ctx* ctx, const tf_params* p, const void* Q, const void* K,
+                                const void* V, uint8_t* keep, int32_t* kept_idx, float* fused,
+                                float* tau, void* O, void* ws, size_t ws_bytes, void* stream)
+{
+    Workspace w;
+    tf_status st = enter(ctx, p, ws, ws_bytes, &w);
+    if (st != TF_OK) return st;
+    if (!Q || !K || !V || !O || !keep || !kept_idx || !fused)
+        return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V, O, keep, kept_idx and fused must not be NULL");
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O))
+        return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V and O must be 16-byte aligned");
+    const tf::Dims d = make_dims(p, tf_keep_count(p->seq, p->prune_ratio));
+    hipStream_t s = (hipStream_t)stream;
+    char* base = (char*)ws;
+    float* sk = (float*)(base + w.sim_k);
+    float* sv = (float*)(base + w.sim_v);
+
+    int slot = -1;
+    if (ctx->timing_on && ctx->timing_calls < kMaxTimedCalls) slot = ctx->timing_calls++;
+
+    mark(ctx, slot, 0, s);
+    st = dev(ctx, tf::launch_score(d, p->dtype, K, V, sk, sv, (float*)(base + w.seg_tot), s), "score launch");
+    if (st != TF_OK) return st;
+    mark(ctx, slot, 1, s);
+    st = dev(ctx, tf::launch_fuse(d, p->fusion, sk, sv, fused, s), "fuse launch");
+    if (st != TF_OK) return st;
+    mark(ctx, slot, 2, s);
+    st = dev(ctx, tf::launch_select(d, p->warmup, fused, keep, tau, s), "select launch");
+    if (st != TF_OK) return st;
+    mark(ctx, slot, 3, s);
+    st = dev(ctx, tf::launch_compact(d, keep, kept_idx, s), "compact launch");
+    if (st != TF_OK) return st;
+    mark(ctx, slot, 4, s);
+    st = run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, s);
+    if (st != TF_OK) return st;
+    mark(ctx, slot, 5, s);
+    return TF_OK;
+}
+
+tf_status tf_stage_timing_enable(tf_ctx* ctx, int on)
+{
+    if (!ctx) return TF_ERR_INVALID_ARG;
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, TF_ERR_DEVICE, "hipSetDevice failed");
+    if (on && !ctx->ev_ready) {
+        for (int i = 0; i < kMaxTimedCalls; ++i)
+            for (int j = 0; j <= TF_N_STAGES; ++j)
+                if (hipEventCreate(&ctx->ev[i][j]) != hipSuccess) return fail(ctx, TF_ERR_DEVICE, "hipEventCreate failed");
+        ctx->ev_ready = true;
+    }
+    ctx->timing_on = on ? 1 : 0;
+    ctx->timing_calls = 0;
+    return TF_OK;
+}
+
+tf_status tf_stage_timing_read(tf_ctx* ctx, float* ms, int32_t* n_calls)
+{
+    if (!ctx || !ms || !n_calls) return TF_ERR_INVALID_ARG;
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, TF_ERR_DEVICE, "hipSetDevice failed");
+    for (int j = 0; j < TF_N_STAGES; ++j) ms[j] = 0.f;
+    for (int i = 0; i < ctx->timing_calls; ++i) {
+        if (hipEventSynchronize(ctx->ev[i][TF_N_STAGES]) != hipSuccess)
+            return fail(ctx, TF_ERR_DEVICE, "hipEventSynchronize failed");
+        for (int j = 0; j < TF_N_STAGES; ++j) {
+            float t = 0.f;
+            if (hipEventElapsedTime(&t, ctx->ev[i][j], ctx->ev[i][j + 1]) != hipSuccess)
+                return fail(ctx, TF_ERR_DEVICE, "hipEventElapsedTime failed");
+            ms[j] += t;
+        }
+    }
+    *n_calls = ctx->timing_calls;
+    ctx->timing_calls = 0;
+    return TF_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,336 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the C ABI.
+
+Tolerances (the benchmark definition's):
+  * fused scores and per-head cosines: |gpu - oracle| <= 1e-5 * |oracle| + 1e-6.  The absolute
+    floor is there because a cosine near zero is a cancelling sum: its error scales with
+    |a||x| (about eps * sqrt(d)), not with the result;
+  * keep mask / kept indices: bit-exact, except that tokens whose oracle score lies within 1e-5
+    of the oracle threshold may swap; the kept count is always exactly m;
+  * attention output: max-abs 1e-4 (fp32), 2e-2 (bf16).
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2512_07090_amd import binding as B
+from paper_2512_07090_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+SCORE_RTOL, SCORE_ATOL = 1e-5, 1e-6
+BAND = 1e-5
+ATTN_TOL = {torch.float32: 1e-4, torch.bfloat16: 2e-2}
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    c = B.Context(0)
+    yield c
+    c.close()
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def assert_scores_close(got, ref, what):
+    got = np.asarray(got, dtype=np.float64)
+    err = np.abs(got - ref)
+    tol = SCORE_RTOL * np.abs(ref) + SCORE_ATOL
+    worst = np.argmax(err - tol)
+    assert np.all(err <= tol), "%s: worst err %.3e at %s (ref %.6f)" % (
+        what, err.flat[worst], np.unravel_index(worst, ref.shape), ref.flat[worst])
+
+
+def assert_mask_parity(keep_gpu, idx_gpu, S_ref, ratio, warmup, keep_ref, tau_ref):
+    """Bit-exact outside the band around the threshold; count exact; indices consistent."""
+    B_, n = keep_ref.shape
+    m = oracle.keep_count(n, ratio)
+    for b in range(B_):
+        assert int(keep_gpu[b].sum()) == m
+        np.testing.assert_array_equal(idx_gpu[b], np.nonzero(keep_gpu[b])[0])
+        diff = np.nonzero(keep_gpu[b] != keep_ref[b])[0]
+        if len(diff):
+            s32 = S_ref[b].astype(np.float32).astype(np.float64)
+            assert np.all(np.abs(s32[diff] - float(tau_ref[b])) <= BAND), (
+                "mask differs outside the threshold band at", diff[:8])
+
+
+def run_path(ctx, q, k, v, ratio, warmup=1, fusion=B.TF_FUSE_EQ2, scale=0.0):
+    dev = "cuda:0"
+    qd, kd, vd = q.to(dev), k.to(dev), v.to(dev)
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, ratio, warmup, fusion, scale)
+    buf = B.Buffers(p, dev)
+    buf.O.fill_(float("nan"))
+    ctx.tf_filtered_attention(p, qd, kd, vd, buf.keep, buf.kept_idx, buf.fused, buf.tau, buf.O,
+                              buf.ws)
+    torch.cuda.synchronize()
+    return p, buf
+
+
+def check_whole_path(ctx, q, k, v, ratio, warmup=1, fusion=B.TF_FUSE_EQ2, scale=0.0):
+    p, buf = run_path(ctx, q, k, v, ratio, warmup, fusion, scale)
+    ref = oracle.filtered_attention(q, k, v, ratio, warmup, fusion, scale, with_attention=False)
+    assert_scores_close(buf.fused.cpu().numpy(), ref["fused"], "fused")
+    keep_g, idx_g = buf.keep.cpu().numpy(), buf.kept_idx.cpu().numpy()
+    assert_mask_parity(keep_g, idx_g, ref["fused"], ratio, warmup, ref["keep"], ref["tau"])
+    tau_g = buf.tau.cpu().numpy()
+    for b in range(q.shape[0]):
+        if np.isfinite(ref["tau"][b]):
+            assert abs(float(tau_g[b]) - float(ref["tau"][b])) <= BAND
+        else:
+            assert tau_g[b] == ref["tau"][b]
+    # attention is checked on the GPU's own kept set (identical to the oracle's outside the band)
+    O_ref = oracle.attend(q, k, v, idx_g, scale)
+    O_g = buf.O.float().cpu().numpy().astype(np.float64)
+    assert not np.isnan(O_g).any(), "some output rows were never written"
+    err = np.abs(O_g - O_ref).max()
+    assert err <= ATTN_TOL[q.dtype], "attention max-abs err %.3e" % err
+    for b in range(q.shape[0]):
+        filt = np.nonzero(keep_g[b] == 0)[0]
+        assert np.all(O_g[b][:, filt] == 0.0)
+    return buf, ref
+
+
+# ------------------------------------------------------------------ scoring stage
+
+@pytest.mark.parametrize("shape", [
+    # (dtype, B, Hq, Hkv, n)   n chosen to span several 128-row tiles and a ragged tail
+    ("f32", 1, 4, 4, 1), ("f32", 1, 4, 4, 7), ("f32", 2, 4, 2, 300), ("bf16", 2, 8, 2, 1000),
+    ("bf16", 1, 32, 8, 4133), ("f32", 1, 2, 1, 2049),
+])
+def test_score_parity_small(ctx, shape):
+    dt, Bn, Hq, Hkv, n = shape
+    _say("score %s" % (shape,))
+    q, k, v, _ = synth.make_random_qkv(Bn, Hq, Hkv, n, 128, dtype=dt, seed=100 + n)
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.5)
+    buf = B.Buffers(p, "cuda:0", with_sims=True)
+    for mode in (B.TF_FUSE_EQ2, B.TF_FUSE_INVVAR, B.TF_FUSE_KEY_ONLY, B.TF_FUSE_VALUE_ONLY):
+        p.fusion = mode
+        ctx.tf_score(p, k.cuda(), v.cuda(), buf.fused, buf.sim_k, buf.sim_v, buf.ws)
+        torch.cuda.synchronize()
+        ck, cv = oracle.anchor_cosine(k), oracle.anchor_cosine(v)
+        assert_scores_close(buf.sim_k.cpu().numpy(), ck, "sim_k")
+        assert_scores_close(buf.sim_v.cpu().numpy(), cv, "sim_v")
+        assert_scores_close(buf.fused.cpu().numpy(), oracle.fuse(ck, cv, mode), "fused mode %d" % mode)
+
+
+def test_score_degenerate_inputs(ctx):
+    _say("score degenerate")
+    n = 200
+    row = torch.randn(128)
+    k = row.expand(1, 2, n, 128).contiguous()           # identical tokens: cosine 1 after the first
+    v = torch.zeros(1, 2, n, 128)                        # all-zero rows: cosine 0 through the guard
+    v[0, 0, 5] = 1.0
+    p = B.make_params((1, 2, n, 128), (1, 2, n, 128), torch.float32, 0.5)
+    buf = B.Buffers(p, "cuda:0", with_sims=True)
+    ctx.tf_score(p, k.cuda(), v.cuda(), buf.fused, buf.sim_k, buf.sim_v, buf.ws)
+    torch.cuda.synchronize()
+    sk, sv = buf.sim_k.cpu().numpy(), buf.sim_v.cpu().numpy()
+    assert np.all(sk[:, :, 0] == 0) and np.all(np.abs(sk[:, :, 1:] - 1) <= 1e-6)
+    assert_scores_close(sv, oracle.anchor_cosine(v), "sim_v zero rows")
+    assert np.all(np.abs(sk) <= 1) and np.all(np.abs(sv) <= 1)
+
+
+# ------------------------------------------------------------------ decision + compaction
+
+@pytest.mark.parametrize("case", [(1, 512, 0.5, 1), (3, 1000, 0.25, 1), (2, 4096, 0.5, 4),
+                                  (1, 33, 0.9, 1), (2, 17, 0.0, 1), (1, 40, 0.5, 0),
+                                  (1, 12, 0.8, 5), (1, 1, 0.5, 1), (1, 5000, 0.999, 1),
+                                  (1, 32768, 0.5, 1)])
+def test_select_bit_exact_on_identical_scores(ctx, case):
+    """Same float scores in, so the decision must agree bit for bit, ties included."""
+    Bn, n, r, W = case
+    _say("select %s" % (case,))
+    rng = np.random.default_rng(n)
+    S = rng.uniform(-1, 1, (Bn, n)).astype(np.float32)
+    S[0] = np.round(S[0] * 8) / 8                        # heavy ties
+    if n > 3:
+        S[-1, 2] = -0.0
+        S[-1, 3] = 0.0
+    keep_r, idx_r, tau_r = oracle.select(S, r, W)
+    p = B.make_params((Bn, 1, n, 128), (Bn, 1, n, 128), torch.float32, r, W)
+    buf = B.Buffers(p, "cuda:0")
+    ctx.tf_select(p, torch.from_numpy(S).cuda(), buf.keep, buf.kept_idx, buf.tau, buf.ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(buf.keep.cpu().numpy(), keep_r)
+    np.testing.assert_array_equal(buf.kept_idx.cpu().numpy(), idx_r)
+    np.testing.assert_array_equal(buf.tau.cpu().numpy(), tau_r)
+
+
+# ------------------------------------------------------------------ attention stage
+
+@pytest.mark.parametrize("shape", [
+    ("f32", 1, 4, 4, 100, 0.5), ("f32", 2, 4, 2, 300, 0.3), ("bf16", 1, 4, 4, 100, 0.5),
+    ("bf16", 2, 8, 2, 700, 0.4), ("bf16", 1, 4, 1, 1500, 0.25), ("bf16", 1, 2, 2, 130, 0.0),
+    ("f32", 1, 2, 2, 1, 0.0), ("bf16", 1, 2, 2, 1, 0.0),
+])
+def test_attend_parity_on_oracle_kept_set(ctx, shape):
+    dt, Bn, Hq, Hkv, n, r = shape
+    _say("attend %s" % (shape,))
+    q, k, v, _ = synth.make_random_qkv(Bn, Hq, Hkv, n, 128, dtype=dt, seed=200 + n)
+    ref = oracle.filtered_attention(q, k, v, r)
+    idx = ref["kept_idx"]
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, r)
+    buf = B.Buffers(p, "cuda:0")
+    buf.O.fill_(float("nan"))
+    ctx.tf_attend(p, q.cuda(), k.cuda(), v.cuda(), torch.from_numpy(idx).cuda(), idx.shape[1],
+                  buf.O, buf.ws)
+    torch.cuda.synchronize()
+    O_g = buf.O.float().cpu().numpy().astype(np.float64)
+    assert not np.isnan(O_g).any()
+    err = np.abs(O_g - ref["O"]).max()
+    assert err <= ATTN_TOL[q.dtype], "max-abs err %.3e" % err
+
+
+def test_attend_softmax_scale_and_single_kept(ctx):
+    _say("attend scale / m=1")
+    q, k, v, _ = synth.make_random_qkv(1, 2, 2, 64, 128, dtype="bf16", seed=7)
+    idx = np.array([[5]], dtype=np.int32)
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.5, softmax_scale=0.05)
+    buf = B.Buffers(p, "cuda:0")
+    ctx.tf_attend(p, q.cuda(), k.cuda(), v.cuda(), torch.from_numpy(idx).cuda(), 1, buf.O, buf.ws)
+    torch.cuda.synchronize()
+    O_g = buf.O.float().cpu().numpy()
+    np.testing.assert_array_equal(O_g[0, :, 5], v[0, :, 5].float().numpy())  # attends itself only
+    assert np.all(np.delete(O_g, 5, axis=2) == 0)
+    idx = np.sort(np.random.default_rng(1).choice(64, 40, replace=False)).astype(np.int32)[None]
+    ctx.tf_attend(p, q.cuda(), k.cuda(), v.cuda(), torch.from_numpy(idx).cuda(), 40, buf.O, buf.ws)
+    torch.cuda.synchronize()
+    ref = oracle.attend(q, k, v, idx, scale=0.05)
+    assert np.abs(buf.O.float().cpu().numpy() - ref).max() <= 2e-2
+
+
+# ------------------------------------------------------------------ whole path
+
+def test_whole_path_workload_1_fp32(ctx):
+    _say("whole path cfg1")
+    w = synth.workload(0)
+    q, k, v, _ = synth.make_qkv(w)
+    for mode in (B.TF_FUSE_EQ2, B.TF_FUSE_INVVAR):
+        check_whole_path(ctx, q, k, v, 0.5, fusion=mode)
+
+
+@pytest.mark.parametrize("wl", [
+    (1, dict(batch=2, seq=1024)), (2, dict(batch=1, seq=1024)), (3, dict(batch=1, seq=2048)),
+    (4, dict(seq=4096)),
+])
+def test_whole_path_reduced_bf16_workloads(ctx, wl):
+    i, changes = wl
+    w = synth.scaled(synth.workload(i), **changes)
+    _say("whole path %s %s" % (w.name, changes))
+    q, k, v, _ = synth.make_qkv(w)
+    for r in w.prune_ratios:
+        check_whole_path(ctx, q, k, v, r)
+
+
+@pytest.mark.parametrize("case", [
+    ("f32", 1, 4, 4, 257, 0.0, 1), ("bf16", 1, 4, 2, 257, 0.0, 1), ("f32", 1, 2, 2, 1, 0.5, 1),
+    ("bf16", 2, 4, 4, 300, 0.99, 1), ("bf16", 1, 4, 4, 300, 0.5, 0), ("f32", 1, 4, 4, 300, 0.5, 64),
+    ("bf16", 1, 4, 4, 64, 0.9, 30),
+])
+def test_whole_path_edge_cases(ctx, case):
+    dt, Bn, Hq, Hkv, n, r, W = case
+    _say("edge %s" % (case,))
+    q, k, v, _ = synth.make_random_qkv(Bn, Hq, Hkv, n, 128, dtype=dt, seed=300 + n)
+    check_whole_path(ctx, q, k, v, r, warmup=W)
+
+
+def test_strided_layout_bnhd(ctx):
+    """[B, n, H, d] storage through the stride arguments gives the same results."""
+    _say("strided layout")
+    q, k, v, _ = synth.make_random_qkv(2, 4, 2, 400, 128, dtype="bf16", seed=9)
+    p0, ref = run_path(ctx, q, k, v, 0.5)
+    Bn, Hq, n, d = q.shape
+    Hkv = k.shape[1]
+    qs, ks, vs = (t.permute(0, 2, 1, 3).contiguous().cuda() for t in (q, k, v))
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.5,
+                      q_stride=(n * Hq * d, d, Hq * d), kv_stride=(n * Hkv * d, d, Hkv * d),
+                      o_stride=(n * Hq * d, d, Hq * d))
+    buf = B.Buffers(p, "cuda:0")
+    O = torch.empty((Bn, n, Hq, d), dtype=q.dtype, device="cuda:0")
+    ctx.tf_filtered_attention(p, qs, ks, vs, buf.keep, buf.kept_idx, buf.fused, buf.tau, O, buf.ws)
+    torch.cuda.synchronize()
+    assert torch.equal(buf.keep, ref.keep) and torch.equal(buf.kept_idx, ref.kept_idx)
+    assert torch.equal(buf.fused, ref.fused)
+    assert torch.equal(O.permute(0, 2, 1, 3), ref.O)
+
+
+def test_deterministic_rerun(ctx):
+    _say("determinism")
+    w = synth.scaled(synth.workload(1), batch=1, seq=2048)
+    q, k, v, _ = synth.make_qkv(w)
+    _, a = run_path(ctx, q, k, v, 0.5)
+    _, b = run_path(ctx, q, k, v, 0.5)
+    for name in ("keep", "kept_idx", "fused", "tau", "O"):
+        assert torch.equal(getattr(a, name), getattr(b, name)), name
+
+
+def test_errors_leave_outputs_untouched(ctx):
+    _say("error paths")
+    q, k, v, _ = synth.make_random_qkv(1, 2, 2, 64, 128, dtype="bf16", seed=5)
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.5)
+    buf = B.Buffers(p, "cuda:0")
+    buf.fused.fill_(7.0)
+    buf.keep.fill_(9)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+
+    def expect(status, fn):
+        with pytest.raises(B.TokfiltError) as e:
+            fn()
+        assert e.value.status == status
+        torch.cuda.synchronize()
+        assert torch.all(buf.fused == 7.0) and torch.all(buf.keep == 9)
+
+    small = torch.empty(16, dtype=torch.uint8, device="cuda:0")
+    expect(B.TF_ERR_WORKSPACE_TOO_SMALL, lambda: ctx.tf_filtered_attention(
+        p, qd, kd, vd, buf.keep, buf.kept_idx, buf.fused, buf.tau, buf.O, small))
+    assert "workspace" in ctx.tf_last_error()
+    expect(B.TF_ERR_INVALID_ARG, lambda: ctx.tf_filtered_attention(
+        p, qd, None, vd, buf.keep, buf.kept_idx, buf.fused, buf.tau, buf.O, buf.ws))
+    expect(B.TF_ERR_INVALID_ARG, lambda: ctx.tf_score(p, kd, vd, None, None, None, buf.ws))
+    bad = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 1.5)
+    expect(B.TF_ERR_INVALID_ARG, lambda: ctx.tf_filtered_attention(
+        bad, qd, kd, vd, buf.keep, buf.kept_idx, buf.fused, buf.tau, buf.O, buf.ws))
+    bad = B.make_params((1, 2, 64, 64), (1, 2, 64, 64), q.dtype, 0.5)
+    expect(B.TF_ERR_UNSUPPORTED, lambda: ctx.tf_score(bad, kd, vd, buf.fused, None, None, buf.ws))
+    expect(B.TF_ERR_INVALID_ARG, lambda: ctx.tf_attend(p, qd, kd, vd, buf.kept_idx, 0, buf.O, buf.ws))
+    expect(B.TF_ERR_INVALID_ARG, lambda: ctx.tf_attend(p, qd, kd, vd, buf.kept_idx, 65, buf.O, buf.ws))
+
+
+# ------------------------------------------------------------------ full benchmark size
+
+def test_full_size_workload_2_sampled(ctx):
+    """The benchmark workload at full size, in the launch configuration bench.py times:
+    scores and mask against the full oracle decision, attention on sampled output rows."""
+    w = synth.workload(1)
+    _say("full size %s" % w.name)
+    q, k, v, _ = synth.make_qkv(w)
+    for r in (0.5, 0.25):
+        p, buf = run_path(ctx, q, k, v, r)
+        ref = oracle.filtered_attention(q, k, v, r, with_attention=False)
+        assert_scores_close(buf.fused.cpu().numpy(), ref["fused"], "fused")
+        keep_g, idx_g = buf.keep.cpu().numpy(), buf.kept_idx.cpu().numpy()
+        assert_mask_parity(keep_g, idx_g, ref["fused"], r, 1, ref["keep"], ref["tau"])
+        m = idx_g.shape[1]
+        rng = np.random.default_rng(42)
+        rows = np.stack([rng.integers(0, w.batch, 384), rng.integers(0, w.n_q_heads, 384),
+                         rng.integers(0, m, 384)], axis=1).astype(np.int32)
+        rows[:8, 2] = [0, 1, 127, 128, 129, m - 129, m - 2, m - 1]      # tile edges
+        want = oracle.attend_rows(q, k, v, idx_g, rows)
+        O = buf.O
+        got = np.stack([O[b, h, idx_g[b, i]].float().cpu().numpy() for b, h, i in rows])
+        err = np.abs(got - want).max()
+        assert err <= 2e-2, "sampled attention rows: max-abs err %.3e" % err
+        # properties that hold at any size: filtered rows are zero, kept rows are written
+        b = 3
+        filt = torch.from_numpy(np.nonzero(keep_g[b] == 0)[0]).cuda()
+        assert torch.all(O[b][:, filt] == 0)
+        kept = torch.from_numpy(idx_g[b].astype(np.int64)).cuda()
+        assert torch.isfinite(O[b][:, kept].float()).all()
+        del buf
+        torch.cuda.empty_cache()
