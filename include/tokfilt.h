@@ -82,7 +82,7 @@ typedef struct {
 
 /* Stages of the path, the order of tf_stage_timing_read's output. */
 enum { TF_STAGE_SCORE = 0, TF_STAGE_FUSE = 1, TF_STAGE_SELECT = 2, TF_STAGE_COMPACT = 3,
-       TF_STAGE_ATTEND = 4, TF_N_STAGES = 5 };
+       TF_STAGE_ZERO_ROWS = 4, TF_STAGE_ATTEND = 5, TF_N_STAGES = 6 };
 
 /* Create a context bound to HIP device `device` (made current for the calling thread inside
  * each call).  *out is set only on TF_OK.  tf_destroy(NULL) is a no-op. */

@@ -18,8 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libtokfilt.so")
 TF_OK, TF_ERR_INVALID_ARG, TF_ERR_UNSUPPORTED, TF_ERR_WORKSPACE_TOO_SMALL, TF_ERR_DEVICE = range(5)
 TF_F32, TF_BF16 = 0, 1
 TF_FUSE_EQ2, TF_FUSE_INVVAR, TF_FUSE_KEY_ONLY, TF_FUSE_VALUE_ONLY = range(4)
-TF_N_STAGES = 5
-STAGE_NAMES = ("score", "fuse", "select", "compact", "attend")
+TF_N_STAGES = 6
+STAGE_NAMES = ("score", "fuse", "select", "compact", "zero_rows", "attend")
 
 EXPORTS = ("tf_create", "tf_destroy", "tf_status_string", "tf_last_error", "tf_keep_count",
            "tf_workspace_bytes", "tf_score", "tf_select", "tf_attend", "tf_filtered_attention",

@@ -123,22 +123,23 @@ tf_status dev(tf_ctx* ctx, hipError_t e, const char* what)
     return fail(ctx, TF_ERR_DEVICE, "%s: %s", what, hipGetErrorString(e));
 }
 
+void mark(tf_ctx* ctx, int slot, int stage, hipStream_t s)
+{
+    if (slot >= 0) (void)hipEventRecord(ctx->ev[slot][stage], s);
+}
+
 tf_status run_attend(tf_ctx* ctx, const tf_params* p, const tf::Dims& d, const void* Q,
                      const void* K, const void* V, const int32_t* kept_idx,
-                     const uint8_t* keep, void* O, hipStream_t s)
+                     const uint8_t* keep, void* O, hipStream_t s, int slot)
 {
     tf_status st = dev(ctx, tf::launch_zero_filtered(d, p->dtype, keep, O, s), "zero-fill launch");
     if (st != TF_OK) return st;
+    mark(ctx, slot, TF_STAGE_ATTEND, s);
     const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
     if (p->dtype == TF_F32)
         return dev(ctx, tf::launch_attend_f32(d, scale, (const float*)Q, (const float*)K, (const float*)V,
                                               kept_idx, (float*)O, s), "fp32 attention launch");
     return dev(ctx, tf::launch_attend_bf16(d, scale, Q, K, V, kept_idx, O, s), "bf16 attention launch");
-}
-
-void mark(tf_ctx* ctx, int slot, int stage, hipStream_t s)
-{
-    if (slot >= 0) (void)hipEventRecord(ctx->ev[slot][stage], s);
 }
 
 }  // namespace
@@ -244,7 +245,7 @@ tf_status tf_attend(tf_ctx* ctx, const tf_params* p, const void* Q, const void* 
     uint8_t* keep = (uint8_t*)((char*)ws + w.keep_tmp);
     st = dev(ctx, tf::launch_mask_from_idx(d, kept_idx, keep, s), "mask launch");
     if (st != TF_OK) return st;
-    return run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, s);
+    return run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, s, -1);
 }
 
 tf_status tf_filtered_attention(tf_ctx* ctx, const tf_params* p, const void* Q, const void* K,
@@ -280,9 +281,9 @@ tf_status tf_filtered_attention(tf_ctx* ctx, const tf_params* p, const void* Q, 
     st = dev(ctx, tf::launch_compact(d, keep, kept_idx, s), "compact launch");
     if (st != TF_OK) return st;
     mark(ctx, slot, 4, s);
-    st = run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, s);
+    st = run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, s, slot);
     if (st != TF_OK) return st;
-    mark(ctx, slot, 5, s);
+    mark(ctx, slot, TF_N_STAGES, s);
     return TF_OK;
 }
 
