@@ -1,14 +1,17 @@
 // Causal softmax attention over the kept tokens, bf16 inputs (Section 3.2: the tokens that
-// are not skipped attend as usual; here both queries and keys are the kept tokens, addressed
-// through kept_idx, so "causal" means key rank <= query rank in the compacted order).
+// are not skipped attend as usual and a skipped token's attention output is zero; here both
+// queries and keys are the kept tokens, addressed through kept_idx, so "causal" means key rank
+// <= query rank in the compacted order).
 //
-// Flash-style kernel for gfx950.  One workgroup = NW waves x 32 kept queries; it walks the key
-// tiles (64 kept keys) once, K and V rows gathered through kept_idx into LDS (row-major,
-// two stages each).
+// Flash-style kernel for gfx950.  One workgroup covers 256 kept queries: 8 / U waves, each
+// owning U sub-tiles of 32 queries (U = 1: two waves per SIMD, 256 registers each; U = 2: one
+// wave per SIMD with the whole register file and half the LDS traffic).  It walks the key tiles
+// (64 kept keys) once, K and V rows gathered through kept_idx into LDS (row-major, two stages
+// each).
 //   S^T = K Q^T   v_mfma_f32_32x32x16_bf16, A = K rows from LDS, B = Q fragments held in
 //                 registers for the whole kernel.  The transposed product puts one query per
 //                 lane column, so the online-softmax row statistics need a single cross-lane
-//                 exchange (lane <-> lane + 32) per tile.
+//                 exchange (lane <-> lane + 32) per step.
 //   O^T += V^T P^T  A = V^T fragments read from the row-major V tile with the LDS transpose
 //                 read (ds_read_b64_tr_b16), B = P^T converted to bf16 straight from the S^T
 //                 accumulator registers.  The contraction order over keys is permuted the same
@@ -16,14 +19,17 @@
 //                 8 (v / 4) + 4 (lane / 32) + v % 4), which is free because a sum is taken.
 //   softmax       fp32, base 2 (scale * log2 e folded into one FMA per score), running max
 //                 only moved when it grows by more than 2^8 so the O rescale is rare.
-//   pipeline      The math advances in halves of a tile (32 keys), the scores running one half
-//                 ahead of the rest, so that every MFMA block has independent VALU work next
-//                 to it and the matrix and vector pipes overlap inside one wave:
-//                   S(next half) = K Q^T  ||  P = exp2(S(this half) - max), row sums, bf16
-//                   O += P V(this half)   ||  causal mask and row max of S(next half)
-//                 K sits in three LDS stages (K(kt) second half and K(kt+1) first half are read
-//                 while K(kt+2) lands), V in two; the next tiles travel from global memory to
-//                 registers during the iteration and are written to LDS at its end.
+//   pipeline      The math advances in steps of 32 keys.  Scores run one step ahead of the
+//                 rest and LDS fragment reads one block ahead of their MFMAs, so every MFMA
+//                 block has independent VALU and LDS work next to it:
+//                   block 1: S(h + 1) = K Q^T  ||  P = exp2(S(h) - max), sums, bf16
+//                            ||  read V(h) fragments
+//                   block 2: O += P V(h)       ||  causal mask and row max of S(h + 1)
+//                            ||  read K(h + 2) fragments
+//                 Tiles travel global -> registers -> LDS two iterations ahead of their use
+//                 (two register sets), so an L2 miss has two iterations to arrive.
+//   zero rows     Workgroups past the attention grid write the zero rows of filtered positions
+//                 (they are dispatched last and fill the tail of the launch).
 #include "tf_kernels.h"
 
 namespace tf {
@@ -35,11 +41,14 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
+constexpr int kBM = 256;                 // kept queries per workgroup
 constexpr int kBN = 64;                  // kept keys per tile
 constexpr int kKStr = kHeadDim + 8;      // K tile row stride, elements (272 B)
 constexpr int kVStr = kHeadDim + 32;     // V tile row stride, elements (320 B)
 constexpr int kKTile = kBN * kKStr;      // elements per K tile
 constexpr int kVTile = kBN * kVStr;      // elements per V tile
+constexpr int kOStr = kHeadDim + 8;      // output staging row stride, elements
+constexpr int kZeroRows = 1024;          // positions per zero-fill workgroup
 constexpr float kMaxSlack = 8.0f;        // running max may lag the true max by 2^8
 constexpr float kMasked = -1e30f;
 
@@ -51,23 +60,92 @@ __device__ __forceinline__ i16x4 lds_read_tr16(const uint16_t* p)
         (__attribute__((address_space(3))) i16x4*)(p));
 }
 
-template <int NW>
-__global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(
-    Dims d, float scale_log2, int n_qt, int total_blocks, const uint16_t* __restrict__ Q,
-    const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-    const int32_t* __restrict__ kept_idx, uint16_t* __restrict__ O)
+// The 16-byte chunks a thread moves per tile of one tensor, and the kept positions of their
+// rows.  Plain members (no arrays) and by-value passing keep them in registers.
+template <int CH>
+struct Rows;
+template <>
+struct Rows<2> { uint4 r0, r1; };
+template <>
+struct Rows<4> { uint4 r0, r1, r2, r3; };
+template <int CH>
+struct Pos;
+template <>
+struct Pos<2> { int p0, p1; };
+template <>
+struct Pos<4> { int p0, p1, p2, p3; };
+
+__device__ __forceinline__ Pos<2> load_pos(const int32_t* idx, int j, int step, int last, Pos<2>*)
 {
-    constexpr int NT = 64 * NW;
-    constexpr int BM = 32 * NW;
+    return Pos<2>{idx[min(j, last)], idx[min(j + step, last)]};
+}
+__device__ __forceinline__ Pos<4> load_pos(const int32_t* idx, int j, int step, int last, Pos<4>*)
+{
+    return Pos<4>{idx[min(j, last)], idx[min(j + step, last)], idx[min(j + 2 * step, last)],
+                  idx[min(j + 3 * step, last)]};
+}
+__device__ __forceinline__ uint4 load16(const uint16_t* base, int pos, long long s_t)
+{
+    return *reinterpret_cast<const uint4*>(base + (long long)pos * s_t);
+}
+__device__ __forceinline__ Rows<2> load_rows(const uint16_t* base, Pos<2> p, long long s_t)
+{
+    return Rows<2>{load16(base, p.p0, s_t), load16(base, p.p1, s_t)};
+}
+__device__ __forceinline__ Rows<4> load_rows(const uint16_t* base, Pos<4> p, long long s_t)
+{
+    return Rows<4>{load16(base, p.p0, s_t), load16(base, p.p1, s_t), load16(base, p.p2, s_t),
+                   load16(base, p.p3, s_t)};
+}
+__device__ __forceinline__ void store_rows(Rows<2> r, uint16_t* dst, int step)
+{
+    *reinterpret_cast<uint4*>(dst) = r.r0;
+    *reinterpret_cast<uint4*>(dst + step) = r.r1;
+}
+__device__ __forceinline__ void store_rows(Rows<4> r, uint16_t* dst, int step)
+{
+    *reinterpret_cast<uint4*>(dst) = r.r0;
+    *reinterpret_cast<uint4*>(dst + step) = r.r1;
+    *reinterpret_cast<uint4*>(dst + 2 * step) = r.r2;
+    *reinterpret_cast<uint4*>(dst + 3 * step) = r.r3;
+}
+
+template <int U>
+__global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
+    Dims d, float scale_log2, int n_qt, int attn_blocks, const uint16_t* __restrict__ Q,
+    const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
+    const int32_t* __restrict__ kept_idx, const uint8_t* __restrict__ keep,
+    uint16_t* __restrict__ O)
+{
+    constexpr int NT = 512 / U;    // threads
     constexpr int CH = 1024 / NT;  // 16-byte chunks per thread per tensor per tile
-    __shared__ __attribute__((aligned(16))) uint16_t smem[3 * kKTile + 2 * kVTile];
-    uint16_t* const k_lds = smem;               // 3 stages of K
-    uint16_t* const v_lds = smem + 3 * kKTile;  // 2 stages of V
+    constexpr int WQ = 32 * U;     // queries per wave
+    __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kKTile + 2 * kVTile];
+    uint16_t* const k_lds = smem;               // 2 stages of K
+    uint16_t* const v_lds = smem + 2 * kKTile;  // 2 stages of V
+    static_assert(kBM * kOStr <= 2 * kKTile + 2 * kVTile, "output staging must fit");
+
+    const int tid = threadIdx.x;
+
+    // ---- zero rows of filtered positions (blocks after the attention grid) ----------------
+    if ((int)blockIdx.x >= attn_blocks) {
+        const int z = blockIdx.x - attn_blocks;
+        const int n_zb = (d.n + kZeroRows - 1) / kZeroRows;
+        const int zbh = z / n_zb;
+        const int p0 = (z % n_zb) * kZeroRows;
+        const int p1 = min(p0 + kZeroRows, d.n);
+        uint16_t* Oz = O + (long long)(zbh / d.Hq) * d.os[0] + (long long)(zbh % d.Hq) * d.os[1];
+        const uint8_t* kp = keep + (long long)(zbh / d.Hq) * d.n;
+        const uint4 zero = make_uint4(0, 0, 0, 0);
+        for (int p = p0 + (tid >> 4); p < p1; p += NT / 16)
+            if (!kp[p]) *reinterpret_cast<uint4*>(Oz + (long long)p * d.os[2] + 8 * (tid & 15)) = zero;
+        return;
+    }
 
     // Workgroup ids are dealt round-robin to the 8 XCDs; renumber so that each XCD gets a
     // contiguous run of (batch, head) groups (its L2 then holds that group's K and V), and
     // inside a group start with the last, longest query tile.
-    const int per_xcd = total_blocks >> 3;
+    const int per_xcd = attn_blocks >> 3;
     const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
     const int bh = logical / n_qt;
     if (bh >= d.B * d.Hq) return;
@@ -82,245 +160,266 @@ __global__ __launch_bounds__(64 * NW) void attend_bf16_kernel(
     uint16_t* Ob = O + (long long)b * d.os[0] + (long long)hq * d.os[1];
     const long long s_t = d.kvs[2];
 
-    const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, hh = lane >> 5;
 
-    const int i0 = qt * BM;
-    const int iw = i0 + 32 * wave;   // first query rank of this wave
-    const int iq = iw + col;         // this lane's query rank
-    const int i_last = min(i0 + BM, d.m) - 1;
+    const int i0 = qt * kBM;
+    const int iw = i0 + WQ * wave;   // first query rank of this wave
+    const int i_last = min(i0 + kBM, d.m) - 1;
     const int n_kt = i_last / kBN + 1;
-    const int lim = min(iq, d.m - 1);  // last key rank this lane's query may see
+    const int m_last = d.m - 1;
+    // last key rank each of this lane's queries (one per sub-tile) may see
+    int lim[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) lim[u] = min(iw + 32 * u + col, m_last);
 
-    // tile-load roles: chunk c = tid + NT * i covers row c / 16, columns 8 (c % 16) ..+7.
-    // Rows past the last kept token re-read the last kept row: finite values that the mask
-    // turns into zero weights, so the loads need no branch.
-    // Everything below is spelled out for the two chunks a thread owns (plain scalars keep the
-    // in-flight tiles in registers).
-    static_assert(CH == 2, "tile loads are written for 512 threads");
-    const int row0 = tid >> 4, row1 = (tid + NT) >> 4;
-    const int col0 = (tid & 15) * 8;  // same column slice for both chunks
-    struct Rows { uint4 a, b; };      // chunk 0 / chunk 1 of one tile of one tensor
-    struct Pos { int a, b; };         // kept positions of the two rows
-    auto load_idx = [&](int j0) -> Pos {
-        return Pos{idx[min(j0 + row0, d.m - 1)], idx[min(j0 + row1, d.m - 1)]};
-    };
-    auto load_rows = [&](const uint16_t* base, Pos p) -> Rows {
-        return Rows{*reinterpret_cast<const uint4*>(base + (long long)p.a * s_t + col0),
-                    *reinterpret_cast<const uint4*>(base + (long long)p.b * s_t + col0)};
-    };
-    auto store_rows = [&](Rows r, uint16_t* stage, int stride) {
-        *reinterpret_cast<uint4*>(stage + row0 * stride + col0) = r.a;
-        *reinterpret_cast<uint4*>(stage + row1 * stride + col0) = r.b;
-    };
+    // tile-load roles: chunk i of a thread covers row tid / 16 + (NT / 16) i, columns
+    // 8 (tid % 16) ..+7.  Rows past the last kept token re-read the last kept row: finite
+    // values that the mask turns into zero weights, so the loads need no branch.
+    const int row0 = tid >> 4;
+    const int col0 = (tid & 15) * 8;
+    constexpr int RS = NT / 16;  // row step between a thread's chunks
+    Rows<CH> kreg_a, vreg_a, kreg_b, vreg_b;
+    Pos<CH> pos_k, pos_v, pos_n;
+#define TF_LOAD_IDX(P, J0) P = load_pos(idx, (J0) + row0, RS, m_last, (Pos<CH>*)nullptr)
+#define TF_LOAD_ROWS(R, BASE, P) R = load_rows((BASE) + col0, P, s_t)
+#define TF_STORE_ROWS(R, STAGE, STRIDE) store_rows(R, (STAGE) + row0 * (STRIDE) + col0, RS * (STRIDE))
+#define TF_COPY_POS(DST, SRC) DST = SRC
 
-    // Q fragments (B operand of S^T = K Q^T): lane (col, hh) holds, for k-step s, the 8
-    // elements 16 s + 8 hh .. +7 of query row `col`.
-    bf16x8 qf[8];
-    {
-        const uint16_t* src = Qb + (long long)idx[min(iq, d.m - 1)] * d.qs[2];
+    // ---- prologue, part 1: every index first, then every row load, no wait in between -----
+    int qpos[U];  // positions of this lane's queries
+#pragma unroll
+    for (int u = 0; u < U; ++u) qpos[u] = idx[lim[u]];
+    Pos<CH> pos_0, pos_1;
+    TF_LOAD_IDX(pos_0, 0);
+    TF_LOAD_IDX(pos_1, kBN);
+    TF_LOAD_IDX(pos_v, 2 * kBN);
+    TF_LOAD_IDX(pos_k, 3 * kBN);
+    // Q fragments (B operand of S^T = K Q^T): for sub-tile u, lane (col, hh) holds, for
+    // k-step s, the 8 elements 16 s + 8 hh .. +7 of query row iw + 32 u + col.
+    bf16x8 qf[U][8];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint16_t* src = Qb + (long long)qpos[u] * d.qs[2];
 #pragma unroll
         for (int s = 0; s < 8; ++s)
-            qf[s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(src + 16 * s + 8 * hh));
+            qf[u][s] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4*>(src + 16 * s + 8 * hh));
     }
+    TF_LOAD_ROWS(kreg_a, Kb, pos_0);  // K(0)
+    TF_LOAD_ROWS(vreg_a, Vb, pos_0);  // V(0)
+    TF_LOAD_ROWS(kreg_b, Kb, pos_1);  // K(1)
+    TF_LOAD_ROWS(vreg_b, Vb, pos_1);  // V(1), stays in registers until iteration 0 ends
+    TF_STORE_ROWS(kreg_a, k_lds, kKStr);
+    TF_STORE_ROWS(vreg_a, v_lds, kVStr);
+    TF_STORE_ROWS(kreg_b, k_lds + kKTile, kKStr);
+    TF_LOAD_ROWS(kreg_a, Kb, pos_v);  // K(2), stays in flight
+    __syncthreads();
 
     // LDS offsets of this lane's operand fragments inside a K / V stage
     const int k_off = col * kKStr + 8 * hh;
     const int v_off = (4 * hh + ((lane & 15) >> 2)) * kVStr + 16 * ((lane >> 4) & 1) + 4 * (lane & 3);
 
-    f32x16 oacc[4];
+    f32x16 oacc[U][4];
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+    for (int u = 0; u < U; ++u)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) oacc[dt][v] = 0.f;
-    float m_run = kMasked;  // running max of the RAW scores (may lag, see kMaxSlack)
-    float l_run = 0.f;      // this lane's share of the softmax denominator
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) oacc[u][dt][v] = 0.f;
+    float m_run[U];  // running max of the RAW scores (may lag, see kMaxSlack)
+    float l_run[U];  // this lane's share of the softmax denominators
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        m_run[u] = kMasked;
+        l_run[u] = 0.f;
+    }
 
-    // raw scores S^T (32 keys x 32 queries) of half a tile; ks points at the half's first row
-    auto qk_half = [&](f32x16& sacc, const uint16_t* ks) {
+    bf16x8 kf[8];           // K fragments of the 32 keys whose scores are computed next
+    bf16x8 vf[2][4];        // V^T fragments of the 32 keys being accumulated
+    bf16x8 pf[U][2];        // P^T of the current step, per sub-tile and 16-key k-step
+    f32x16 s_x[U], s_y[U];  // raw scores of two consecutive steps, per sub-tile
+
+    // K fragments of the 32 keys whose first row sits at `ks` in a K stage
+    auto read_kf = [&](const uint16_t* ks) {
 #pragma unroll
-        for (int v = 0; v < 16; ++v) sacc[v] = 0.f;
-#pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            const bf16x8 kf = *reinterpret_cast<const bf16x8*>(ks + k_off + 16 * s);
-            sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sacc, 0, 0, 0);
-        }
+        for (int s = 0; s < 8; ++s) kf[s] = *reinterpret_cast<const bf16x8*>(ks + k_off + 16 * s);
     };
-    // causal / tail mask of the 32 keys starting at rank j0, then their row max.
+    // V^T fragments of the 32 keys starting at `vs`: k-slot e of k-step ks is key
+    // 16 ks + 8 (e / 4) + 4 hh + e % 4, matching the P^T operand
+    auto read_vf = [&](const uint16_t* vs) {
+#pragma unroll
+        for (int ks2 = 0; ks2 < 2; ++ks2)
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+                const uint16_t* vp = vs + v_off + 16 * ks2 * kVStr + 32 * dt;
+                const i16x4 both[2] = {lds_read_tr16(vp), lds_read_tr16(vp + 8 * kVStr)};
+                vf[ks2][dt] = __builtin_bit_cast(bf16x8, both);
+            }
+    };
+    // raw scores of 32 keys from the fragments in kf
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#define TF_QK(S)                                                                               \
+    _Pragma("unroll") for (int u = 0; u < U; ++u)                                              \
+        S[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[0], qf[u][0], zero16, 0, 0, 0);      \
+    _Pragma("unroll") for (int s = 1; s < 8; ++s)                                              \
+        _Pragma("unroll") for (int u = 0; u < U; ++u)                                          \
+            S[u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s], qf[u][s], S[u], 0, 0, 0)
+    // causal / tail mask of the 32 keys starting at rank j0, then the row max.
     // Accumulator register v is key j0 + 8 (v / 4) + 4 hh + v % 4.
-    auto mask_and_max = [&](f32x16& sacc, int j0) -> float {
-        if (j0 + 31 > iw || j0 + 32 > d.m) {
-            const int t = j0 + 4 * hh - lim;  // key rank of register 0 minus the limit
+    auto mask_and_max = [&](f32x16& sacc, int j0, int limit, bool need_mask) -> float {
+        if (need_mask) {
+            const int t = j0 + 4 * hh - limit;  // key rank of register 0 minus the limit
 #pragma unroll
             for (int v = 0; v < 16; ++v)
                 if (t + (8 * (v >> 2) + (v & 3)) > 0) sacc[v] = kMasked;
         }
-        float mx = sacc[0];
+        float mx = fmaxf(sacc[0], sacc[1]);
 #pragma unroll
-        for (int v = 1; v < 16; ++v) mx = fmaxf(mx, sacc[v]);
+        for (int v = 2; v < 16; v += 2) mx = fmaxf(mx, fmaxf(sacc[v], sacc[v + 1]));
         return fmaxf(mx, __shfl_xor(mx, 32));
     };
-    // Move the running max when the new max exceeds it by more than the slack; rescale what
-    // has been accumulated so far.
-    auto update_max = [&](float mx) {
-        const bool grow = (mx - m_run) * scale_log2 > kMaxSlack;
+    // Move a running max when the new max exceeds it by more than the slack; rescale what
+    // has been accumulated so far for that sub-tile.
+    auto update_max = [&](int u, float mx) {
+        const bool grow = (mx - m_run[u]) * scale_log2 > kMaxSlack;
         if (__any(grow)) {
-            const float m_new = grow ? mx : m_run;
-            const float corr = __builtin_amdgcn_exp2f((m_run - m_new) * scale_log2);
-            m_run = m_new;
-            l_run *= corr;
+            const float m_new = grow ? mx : m_run[u];
+            const float corr = __builtin_amdgcn_exp2f((m_run[u] - m_new) * scale_log2);
+            m_run[u] = m_new;
+            l_run[u] *= corr;
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) oacc[dt][v] *= corr;
-        }
-    };
-    // P = exp2((S - max) * scale), this lane's share of the row sums, P^T as bf16 B operands
-    auto softmax_half = [&](const f32x16& sacc, bf16x8* pf) {
-        const float mc = m_run * scale_log2;
-        float psum = 0.f;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const float p = __builtin_amdgcn_exp2f(fmaf(sacc[v], scale_log2, -mc));
-            psum += p;
-            pf[v >> 3][v & 7] = (__bf16)p;
-        }
-        l_run += psum;
-    };
-    // O^T (d x queries) += V^T P^T over 32 keys; vs points at the half's first V row.
-    // k-slot e of k-step ks is key 16 ks + 8 (e / 4) + 4 hh + e % 4 for both operands.
-    auto pv_half = [&](const bf16x8* pf, const uint16_t* vs) {
-#pragma unroll
-        for (int ks2 = 0; ks2 < 2; ++ks2) {
-#pragma unroll
-            for (int dt = 0; dt < 4; ++dt) {
-                const uint16_t* vp = vs + v_off + 16 * ks2 * kVStr + 32 * dt;
-                const i16x4 lo = lds_read_tr16(vp);
-                const i16x4 hi = lds_read_tr16(vp + 8 * kVStr);
-                const i16x4 both[2] = {lo, hi};
-                oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    __builtin_bit_cast(bf16x8, both), pf[ks2], oacc[dt], 0, 0, 0);
-            }
+                for (int v = 0; v < 16; ++v) oacc[u][dt][v] *= corr;
         }
     };
 
-    // ---- prologue: K(0), V(0), K(1) into LDS; K(2), V(1) in flight; S(0, half 0) ----------
-    // Two register sets carry tiles from global memory to LDS, so a tile has two iterations
-    // to arrive: iteration kt issues the loads of K(kt + 3) and V(kt + 2) into one set and, at
-    // its end, writes the other set (K(kt + 2), V(kt + 1), issued one iteration earlier).
-    Rows kreg_a, vreg_a, kreg_b, vreg_b;
-    Pos pos_k, pos_v;  // kept positions of the rows of the next K / V tile to fetch
-    pos_k = load_idx(0);
-    kreg_a = load_rows(Kb, pos_k);
-    vreg_a = load_rows(Vb, pos_k);
-    pos_k = load_idx(kBN);
-    pos_v = load_idx(2 * kBN);
-    store_rows(kreg_a, k_lds, kKStr);
-    store_rows(vreg_a, v_lds, kVStr);
-    kreg_b = load_rows(Kb, pos_k);   // K(1)
-    vreg_a = load_rows(Vb, pos_k);   // V(1), stays in flight
-    kreg_a = load_rows(Kb, pos_v);   // K(2), stays in flight
-    pos_k = load_idx(3 * kBN);
-    store_rows(kreg_b, k_lds + kKTile, kKStr);
-    __syncthreads();
-    f32x16 s_x, s_y;  // scores of half 0 / half 1 of a tile
-    qk_half(s_x, k_lds);
-    update_max(mask_and_max(s_x, 0));
+    // One step over 32 keys.  On entry S_CUR holds the masked raw scores of step h and kf the
+    // K fragments of step h + 1; VS is where V(h) sits in LDS, KS_NEXT where K(h + 2) sits;
+    // J_NEXT is the key rank at which step h + 1 starts.  (A macro: the score registers must
+    // not be reached through pointer arguments.)
+#define TF_STEP(S_CUR, S_NXT, VS, KS_NEXT, J_NEXT, MASK_NEXT)                                   \
+    do {                                                                                       \
+        /* block 1 */                                                                          \
+        read_vf(VS);                                                                           \
+        TF_QK(S_NXT);                                                                          \
+        _Pragma("unroll") for (int u = 0; u < U; ++u) {                                        \
+            const float mc = m_run[u] * scale_log2;                                            \
+            float psum = 0.f;                                                                  \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v) {                                   \
+                const float p = __builtin_amdgcn_exp2f(fmaf(S_CUR[u][v], scale_log2, -mc));    \
+                psum += p;                                                                     \
+                pf[u][v >> 3][v & 7] = (__bf16)p;                                              \
+            }                                                                                  \
+            l_run[u] += psum;                                                                  \
+        }                                                                                      \
+        /* block 2 */                                                                          \
+        read_kf(KS_NEXT);                                                                      \
+        _Pragma("unroll") for (int ks2 = 0; ks2 < 2; ++ks2)                                    \
+            _Pragma("unroll") for (int dt = 0; dt < 4; ++dt)                                   \
+                _Pragma("unroll") for (int u = 0; u < U; ++u)                                  \
+                    oacc[u][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(                     \
+                        vf[ks2][dt], pf[u][ks2], oacc[u][dt], 0, 0, 0);                        \
+        float mx_[U];                                                                          \
+        _Pragma("unroll") for (int u = 0; u < U; ++u)                                          \
+            mx_[u] = mask_and_max(S_NXT[u], J_NEXT, lim[u], MASK_NEXT);                        \
+        _Pragma("unroll") for (int u = 0; u < U; ++u) update_max(u, mx_[u]);                   \
+    } while (0)
 
-    // K stages rotate over three buffers: iteration kt reads K(kt) (its second half) and
-    // K(kt + 1) (its first half) while K(kt + 2) is being written.
-    int ks_cur = 0, ks_nxt = 1, ks_wr = 2;
-#define TF_ISSUE_LOADS(ld_k, ld_v, kt)                                                         \
-    do {                                                                                      \
-        ld_k = load_rows(Kb, pos_k); /* K(kt + 3) */                                          \
-        ld_v = load_rows(Vb, pos_v); /* V(kt + 2) */                                          \
-        pos_v = pos_k;                                                                        \
-        pos_k = load_idx(((kt) + 4) * kBN);                                                   \
-    } while (0)
-#define TF_FINISH(st_k, st_v, kt)                                                              \
-    do {                                                                                      \
-        store_rows(st_k, k_lds + ks_wr * kKTile, kKStr);            /* K(kt + 2) */           \
-        store_rows(st_v, v_lds + (((kt) & 1) ^ 1) * kVTile, kVStr); /* V(kt + 1) */           \
-        __syncthreads();                                                                      \
-        const int t_ = ks_cur;                                                                \
-        ks_cur = ks_nxt;                                                                      \
-        ks_nxt = ks_wr;                                                                       \
-        ks_wr = t_;                                                                           \
-    } while (0)
-    auto compute = [&](int kt) {
-        const int j0 = kt * kBN;
-        const uint16_t* vs = v_lds + (kt & 1) * kVTile;
-        if (j0 + 32 <= iw) {
-            bf16x8 pf[2];
-            // half-step A: S(kt, 1) = K Q^T  ||  P(kt, 0); then O += P V  ||  mask, max of S(kt, 1)
-            qk_half(s_y, k_lds + ks_cur * kKTile + 32 * kKStr);
-            softmax_half(s_x, pf);
-            pv_half(pf, vs);
-            update_max(mask_and_max(s_y, j0 + 32));
-            // half-step B: S(kt + 1, 0)  ||  P(kt, 1); then O += P V  ||  mask, max of S(kt + 1, 0)
-            qk_half(s_x, k_lds + ks_nxt * kKTile);
-            softmax_half(s_y, pf);
-            pv_half(pf, vs + 32 * kVStr);
-            update_max(mask_and_max(s_x, j0 + kBN));
-        } else if (j0 <= iw) {
-            // last tile of this wave: only its first 32 keys are visible
-            bf16x8 pf[2];
-            softmax_half(s_x, pf);
-            pv_half(pf, vs);
-        }
-    };
-    for (int kt = 0; kt < n_kt; kt += 2) {
-        TF_ISSUE_LOADS(kreg_b, vreg_b, kt);
-        compute(kt);
-        TF_FINISH(kreg_a, vreg_a, kt);
-        if (kt + 1 < n_kt) {
-            TF_ISSUE_LOADS(kreg_a, vreg_a, kt + 1);
-            compute(kt + 1);
-            TF_FINISH(kreg_b, vreg_b, kt + 1);
-        }
+    // ---- prologue, part 2: scores of step 0; K fragments of step 1 ------------------------
+    {
+        const bool diag0 = kBN > iw || kBN > d.m;
+        read_kf(k_lds);
+        TF_QK(s_x);
+#pragma unroll
+        for (int u = 0; u < U; ++u) update_max(u, mask_and_max(s_x[u], 0, lim[u], diag0));
+        read_kf(k_lds + 32 * kKStr);
     }
-#undef TF_ISSUE_LOADS
-#undef TF_FINISH
+    __syncthreads();  // K(0) is fully in registers before iteration 0 may overwrite its stage
+
+    // Iteration kt: issue the loads of K(kt + 3) and V(kt + 2) into register set LD, do the two
+    // steps of tile kt, then write set ST (K(kt + 2), V(kt + 1), issued one iteration earlier)
+    // into the stages that K(kt) and V(kt - 1) have left.  Index loads go first so that
+    // waiting for them leaves the row loads in flight.
+#define TF_ITERATION(KT, LD_K, LD_V, ST_K, ST_V)                                                \
+    do {                                                                                       \
+        const int cur = (KT) & 1;                                                              \
+        const int j0 = (KT) * kBN;                                                             \
+        TF_LOAD_IDX(pos_n, j0 + 4 * kBN);                                                      \
+        TF_LOAD_ROWS(LD_K, Kb, pos_k);                                                         \
+        TF_LOAD_ROWS(LD_V, Vb, pos_v);                                                         \
+        TF_COPY_POS(pos_v, pos_k);                                                             \
+        TF_COPY_POS(pos_k, pos_n);                                                             \
+        if (j0 <= iw) {                                                                        \
+            const uint16_t* vs = v_lds + cur * kVTile;                                         \
+            const uint16_t* kn = k_lds + (cur ^ 1) * kKTile;         /* K(kt + 1) */           \
+            const bool m1 = j0 + kBN > iw || j0 + kBN > d.m;         /* this tile is masked */ \
+            const bool m2 = j0 + 2 * kBN > iw || j0 + 2 * kBN > d.m; /* the next one is */     \
+            TF_STEP(s_x, s_y, vs, kn, j0 + 32, m1);                                            \
+            TF_STEP(s_y, s_x, vs + 32 * kVStr, kn + 32 * kKStr, j0 + kBN, m2);                 \
+        }                                                                                      \
+        TF_STORE_ROWS(ST_K, k_lds + cur * kKTile, kKStr);                                      \
+        TF_STORE_ROWS(ST_V, v_lds + (cur ^ 1) * kVTile, kVStr);                                \
+        __syncthreads();                                                                       \
+    } while (0)
+
+    // after the prologue: kreg_a = K(2) is in flight, vreg_b = V(1) is loaded; pos_k / pos_v
+    // hold the rows of tile 3 / tile 2
+    for (int kt = 0; kt < n_kt; kt += 2) {
+        TF_ITERATION(kt, kreg_b, vreg_a, kreg_a, vreg_b);
+        if (kt + 1 < n_kt) TF_ITERATION(kt + 1, kreg_a, vreg_b, kreg_b, vreg_a);
+    }
+#undef TF_ITERATION
+#undef TF_STEP
+#undef TF_QK
+#undef TF_LOAD_IDX
+#undef TF_LOAD_ROWS
+#undef TF_STORE_ROWS
+#undef TF_COPY_POS
 
     // normalise, transpose through LDS (all tiles are consumed) and write whole rows
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    uint16_t* os = smem + wave * (32 * kKStr);  // [32 queries][kKStr]
+    uint16_t* os = smem + wave * (WQ * kOStr);  // [WQ queries][kOStr]
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+    for (int u = 0; u < U; ++u) {
+        const float l_tot = l_run[u] + __shfl_xor(l_run[u], 32);
+        const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
 #pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4) {
-            bf16x4 o4;
+        for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-            for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[dt][4 * v4 + e] * inv);
-            *reinterpret_cast<bf16x4*>(os + col * kKStr + 32 * dt + 8 * v4 + 4 * hh) = o4;
-        }
+            for (int v4 = 0; v4 < 4; ++v4) {
+                bf16x4 o4;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[u][dt][4 * v4 + e] * inv);
+                *reinterpret_cast<bf16x4*>(os + (32 * u + col) * kOStr + 32 * dt + 8 * v4 + 4 * hh) = o4;
+            }
+    }
     __syncthreads();
 #pragma unroll
-    for (int it = 0; it < 8; ++it) {
-        const int r = 4 * it + (lane >> 4);
-        const int i = iw + r;
-        if (i < d.m) {
-            const uint4 v = *reinterpret_cast<const uint4*>(os + r * kKStr + 8 * (lane & 15));
-            *reinterpret_cast<uint4*>(Ob + (long long)idx[i] * d.os[2] + 8 * (lane & 15)) = v;
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int it = 0; it < 8; ++it) {
+            const int r = 4 * it + (lane >> 4);  // query row inside the sub-tile
+            const int p = __shfl(qpos[u], r);    // its position, held by lane r
+            if (iw + 32 * u + r < d.m) {
+                const uint4 v = *reinterpret_cast<const uint4*>(os + (32 * u + r) * kOStr + 8 * (lane & 15));
+                *reinterpret_cast<uint4*>(Ob + (long long)p * d.os[2] + 8 * (lane & 15)) = v;
+            }
         }
-    }
 }
 
 }  // namespace
 
 hipError_t launch_attend_bf16(const Dims& d, float scale, const void* Q, const void* K,
-                              const void* V, const int32_t* kept_idx, void* O, hipStream_t s)
+                              const void* V, const int32_t* kept_idx, const uint8_t* keep, void* O,
+                              hipStream_t s)
 {
-    constexpr int NW = 8;
-    constexpr int BM = 32 * NW;
-    const int n_qt = (d.m + BM - 1) / BM;
-    const int blocks = n_qt * d.Hq * d.B;
-    const int total = (blocks + 7) & ~7;
-    attend_bf16_kernel<NW><<<dim3(total), dim3(64 * NW), 0, s>>>(
-        d, scale * 1.44269504088896340736f, n_qt, total, (const uint16_t*)Q, (const uint16_t*)K,
-        (const uint16_t*)V, kept_idx, (uint16_t*)O);
+    constexpr int U = 1;
+    const int n_qt = (d.m + kBM - 1) / kBM;
+    const int attn = (n_qt * d.Hq * d.B + 7) & ~7;
+    const int zero = d.m < d.n ? d.B * d.Hq * ((d.n + kZeroRows - 1) / kZeroRows) : 0;
+    attend_bf16_kernel<U><<<dim3(attn + zero), dim3(512 / U), 0, s>>>(
+        d, scale * 1.44269504088896340736f, n_qt, attn, (const uint16_t*)Q, (const uint16_t*)K,
+        (const uint16_t*)V, kept_idx, keep, (uint16_t*)O);
     return hipGetLastError();
 }
 

@@ -46,8 +46,10 @@ hipError_t launch_zero_filtered(const Dims& d, int dtype, const uint8_t* keep, v
                                 hipStream_t s);
 hipError_t launch_attend_f32(const Dims& d, float scale, const float* Q, const float* K,
                              const float* V, const int32_t* kept_idx, float* O, hipStream_t s);
+// also writes the zero rows of filtered positions (keep: [B][n] mask)
 hipError_t launch_attend_bf16(const Dims& d, float scale, const void* Q, const void* K,
-                              const void* V, const int32_t* kept_idx, void* O, hipStream_t s);
+                              const void* V, const int32_t* kept_idx, const uint8_t* keep, void* O,
+                              hipStream_t s);
 
 // ---- small device helpers -----------------------------------------------------------------
 #ifdef __HIPCC__

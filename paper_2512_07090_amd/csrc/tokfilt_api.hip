@@ -132,14 +132,17 @@ tf_status run_attend(tf_ctx* ctx, const tf_params* p, const tf::Dims& d, const v
                      const void* K, const void* V, const int32_t* kept_idx,
                      const uint8_t* keep, void* O, hipStream_t s, int slot)
 {
-    tf_status st = dev(ctx, tf::launch_zero_filtered(d, p->dtype, keep, O, s), "zero-fill launch");
-    if (st != TF_OK) return st;
-    mark(ctx, slot, TF_STAGE_ATTEND, s);
     const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
-    if (p->dtype == TF_F32)
+    if (p->dtype == TF_F32) {
+        tf_status st = dev(ctx, tf::launch_zero_filtered(d, p->dtype, keep, O, s), "zero-fill launch");
+        if (st != TF_OK) return st;
+        mark(ctx, slot, TF_STAGE_ATTEND, s);
         return dev(ctx, tf::launch_attend_f32(d, scale, (const float*)Q, (const float*)K, (const float*)V,
                                               kept_idx, (float*)O, s), "fp32 attention launch");
-    return dev(ctx, tf::launch_attend_bf16(d, scale, Q, K, V, kept_idx, O, s), "bf16 attention launch");
+    }
+    // the bf16 kernel writes the zero rows itself, in workgroups at the end of its grid
+    mark(ctx, slot, TF_STAGE_ATTEND, s);
+    return dev(ctx, tf::launch_attend_bf16(d, scale, Q, K, V, kept_idx, keep, O, s), "bf16 attention launch");
 }
 
 }  // namespace
