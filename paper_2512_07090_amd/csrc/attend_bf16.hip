@@ -164,7 +164,12 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
     const int col = lane & 31, hh = lane >> 5;
 
     const int i0 = qt * kBM;
-    const int iw = i0 + WQ * wave;   // first query rank of this wave
+    // Waves w and w + NT / 256 share a SIMD.  Causal work grows with the row block, so the
+    // second half of the waves takes the row blocks in reverse: every SIMD then carries one
+    // early and one late block and the four SIMDs finish together.
+    constexpr int NWV = NT / 64;
+    const int blk = wave < NWV / 2 ? wave : NWV + NWV / 2 - 1 - wave;
+    const int iw = i0 + WQ * blk;    // first query rank of this wave
     const int i_last = min(i0 + kBM, d.m) - 1;
     const int n_kt = i_last / kBN + 1;
     const int m_last = d.m - 1;
