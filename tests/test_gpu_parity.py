@@ -304,13 +304,14 @@ def test_errors_leave_outputs_untouched(ctx):
 
 # ------------------------------------------------------------------ full benchmark size
 
-def test_full_size_workload_2_sampled(ctx):
-    """The benchmark workload at full size, in the launch configuration bench.py times:
-    scores and mask against the full oracle decision, attention on sampled output rows."""
-    w = synth.workload(1)
+def _full_size_case(ctx, w, ratios, n_rows=384):
+    """A workload at its full size, in the launch configuration bench.py times: scores and mask
+    against the full oracle decision, attention on sampled output rows (the oracle computes
+    each row independently), plus properties that hold at any size."""
     _say("full size %s" % w.name)
     q, k, v, _ = synth.make_qkv(w)
-    for r in (0.5, 0.25):
+    g = w.n_q_heads // w.n_kv_heads
+    for r in ratios:
         p, buf = run_path(ctx, q, k, v, r)
         ref = oracle.filtered_attention(q, k, v, r, with_attention=False)
         assert_scores_close(buf.fused.cpu().numpy(), ref["fused"], "fused")
@@ -318,19 +319,39 @@ def test_full_size_workload_2_sampled(ctx):
         assert_mask_parity(keep_g, idx_g, ref["fused"], r, 1, ref["keep"], ref["tau"])
         m = idx_g.shape[1]
         rng = np.random.default_rng(42)
-        rows = np.stack([rng.integers(0, w.batch, 384), rng.integers(0, w.n_q_heads, 384),
-                         rng.integers(0, m, 384)], axis=1).astype(np.int32)
-        rows[:8, 2] = [0, 1, 127, 128, 129, m - 129, m - 2, m - 1]      # tile edges
+        rows = np.stack([rng.integers(0, w.batch, n_rows), rng.integers(0, w.n_q_heads, n_rows),
+                         rng.integers(0, m, n_rows)], axis=1).astype(np.int32)
+        edges = [0, 1, 31, 32, 63, 64, 255, 256, 257, m - 257, m - 256, m - 65, m - 64, m - 2, m - 1]
+        rows[:len(edges), 2] = edges                                     # tile and block edges
         want = oracle.attend_rows(q, k, v, idx_g, rows)
         O = buf.O
         got = np.stack([O[b, h, idx_g[b, i]].float().cpu().numpy() for b, h, i in rows])
         err = np.abs(got - want).max()
-        assert err <= 2e-2, "sampled attention rows: max-abs err %.3e" % err
-        # properties that hold at any size: filtered rows are zero, kept rows are written
-        b = 3
+        assert err <= ATTN_TOL[q.dtype], "sampled attention rows: max-abs err %.3e" % err
+        b = w.batch - 1
         filt = torch.from_numpy(np.nonzero(keep_g[b] == 0)[0]).cuda()
-        assert torch.all(O[b][:, filt] == 0)
+        assert torch.all(O[b][:, filt] == 0)                             # filtered rows are zero
         kept = torch.from_numpy(idx_g[b].astype(np.int64)).cuda()
-        assert torch.isfinite(O[b][:, kept].float()).all()
+        assert torch.isfinite(O[b][:, kept].float()).all()               # kept rows are written
+        # first kept row of every head attends only itself
+        first = int(idx_g[b, 0])
+        vv = v[b, :, first].float().repeat_interleave(g, 0)
+        assert torch.equal(O[b, :, first].float().cpu(), vv.to(O.dtype).float())
         del buf
         torch.cuda.empty_cache()
+
+
+def test_full_size_workload_2_sampled(ctx):
+    _full_size_case(ctx, synth.workload(1), (0.5, 0.25))
+
+
+def test_full_size_workload_3_split_noise_heads(ctx):
+    _full_size_case(ctx, synth.workload(2), (0.5,))
+
+
+def test_full_size_workload_4_gqa(ctx):
+    _full_size_case(ctx, synth.workload(3), (0.5,))
+
+
+def test_full_size_workload_5_long_context_runs(ctx):
+    _full_size_case(ctx, synth.workload(4), (0.5,))
