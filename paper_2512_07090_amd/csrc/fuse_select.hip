@@ -8,39 +8,47 @@ namespace tf {
 namespace {
 
 // ------------------------------------------------------------------------------ fusion
-// One thread per token; the token's per-head cosines are staged in LDS ([head][token] so that
-// both the global reads and the LDS accesses are unit-stride across the wave) because the
-// variance is taken in two passes and the head count is a run-time value.
+// 64 tokens per workgroup.  All 256 threads stage the tokens' per-head cosines in LDS
+// ([head][token]: global reads and LDS accesses are unit-stride across a wave; four head
+// groups load in parallel so enough loads are in flight); then one thread per token takes the
+// mean and the two-pass variance over the heads (the head count is a run-time value).
 constexpr int kFuseTokens = 64;
+constexpr int kFuseThreads = 256;
 
-__global__ __launch_bounds__(kFuseTokens) void fuse_kernel(const float* __restrict__ sim_k,
-                                                           const float* __restrict__ sim_v,
-                                                           int H, int n, int mode,
-                                                           float* __restrict__ fused)
+__global__ __launch_bounds__(kFuseThreads) void fuse_kernel(const float* __restrict__ sim_k,
+                                                            const float* __restrict__ sim_v,
+                                                            int H, int n, int mode,
+                                                            float* __restrict__ fused)
 {
     extern __shared__ float stage[];  // [2][H][kFuseTokens]
     float* ck = stage;
     float* cv = stage + (size_t)H * kFuseTokens;
     const int b = blockIdx.y;
-    const int t = blockIdx.x * kFuseTokens + threadIdx.x;
-    if (t >= n) return;
-    const float* pk = sim_k + (long long)b * H * n + t;
-    const float* pv = sim_v + (long long)b * H * n + t;
+    const int tok = threadIdx.x & (kFuseTokens - 1);
+    const int hg = threadIdx.x / kFuseTokens;
+    const int t = blockIdx.x * kFuseTokens + tok;
+    if (t < n) {
+        const float* pk = sim_k + (long long)b * H * n + t;
+        const float* pv = sim_v + (long long)b * H * n + t;
+        for (int h = hg; h < H; h += kFuseThreads / kFuseTokens) {
+            ck[h * kFuseTokens + tok] = pk[(long long)h * n];
+            cv[h * kFuseTokens + tok] = pv[(long long)h * n];
+        }
+    }
+    __syncthreads();
+    if (hg != 0 || t >= n) return;
     float sk = 0.f, sv = 0.f;
     for (int h = 0; h < H; ++h) {
-        const float a = pk[(long long)h * n], c = pv[(long long)h * n];
-        ck[h * kFuseTokens + threadIdx.x] = a;
-        cv[h * kFuseTokens + threadIdx.x] = c;
-        sk += a;
-        sv += c;
+        sk += ck[h * kFuseTokens + tok];
+        sv += cv[h * kFuseTokens + tok];
     }
     const float inv_h = 1.0f / (float)H;
     sk *= inv_h;
     sv *= inv_h;
     float vk = 0.f, vv = 0.f;
     for (int h = 0; h < H; ++h) {
-        const float dk = ck[h * kFuseTokens + threadIdx.x] - sk;
-        const float dv = cv[h * kFuseTokens + threadIdx.x] - sv;
+        const float dk = ck[h * kFuseTokens + tok] - sk;
+        const float dv = cv[h * kFuseTokens + tok] - sv;
         vk = fmaf(dk, dk, vk);
         vv = fmaf(dv, dv, vv);
     }
@@ -191,6 +199,115 @@ __global__ __launch_bounds__(kSelThreads) void compact_kernel(const uint8_t* __r
     }
 }
 
+// ------------------------------------------------------------------------------ decision + compaction
+// Same decision as select_kernel followed by compact_kernel, in one launch, for rows of up to
+// 1024 * IPT tokens: a thread keeps its IPT consecutive scores in registers, so the four radix
+// passes and the two ordered scans (rank among the threshold's equals, rank among the kept)
+// touch only registers and LDS.
+template <int IPT>
+__global__ __launch_bounds__(kSelThreads) void select_compact_kernel(
+    const float* __restrict__ fused, int n, int m, int warmup, uint8_t* __restrict__ keep,
+    int32_t* __restrict__ kept_idx, float* __restrict__ tau)
+{
+    __shared__ int hist[256];
+    __shared__ int scan_lds[kSelWaves + 1];
+    __shared__ unsigned sel_prefix;
+    __shared__ int sel_k;
+
+    const int b = blockIdx.x;
+    const float* S = fused + (long long)b * n;
+    uint8_t* kp = keep + (long long)b * n;
+    int32_t* out = kept_idx + (long long)b * m;
+    const int tid = threadIdx.x;
+    const int t0 = tid * IPT;
+    const int forced = min(max(warmup, 0), m);
+    const int want = m - forced;
+    const bool all = m >= n;            // nothing is filtered
+    const bool none = want <= 0;        // no non-forced token is kept
+
+    // keys of this thread's tokens; forced tokens and the tail past n take no part in the
+    // selection (cand = false)
+    unsigned key[IPT];
+    bool cand[IPT];
+#pragma unroll
+    for (int i = 0; i < IPT; ++i) {
+        const int t = t0 + i;
+        cand[i] = t >= forced && t < n;
+        key[i] = cand[i] ? f2key(S[t]) : 0xffffffffu;
+    }
+
+    unsigned tkey = 0;
+    int k_eq = 0;
+    if (!all && !none) {
+        unsigned prefix = 0;
+        int k = want;  // 1-based rank still to find inside the current prefix bucket
+        for (int pass = 0; pass < 4; ++pass) {
+            const int shift = 24 - 8 * pass;
+            const unsigned himask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
+            if (tid < 256) hist[tid] = 0;
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < IPT; ++i)
+                if (cand[i] && (key[i] & himask) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1);
+            __syncthreads();
+            const int cnt = tid < 256 ? hist[tid] : 0;
+            int total;
+            const int before = block_excl_scan(cnt, scan_lds, &total);
+            if (tid < 256 && before < k && k <= before + cnt) {
+                sel_prefix = prefix | ((unsigned)tid << shift);
+                sel_k = k - before;
+            }
+            __syncthreads();
+            prefix = sel_prefix;
+            k = sel_k;
+            __syncthreads();
+        }
+        tkey = prefix;
+        k_eq = k;
+    }
+    if (tid == 0 && tau) tau[b] = all ? INFINITY : (none ? -INFINITY : key2f(tkey));
+
+    // rank of this thread's threshold-equal tokens among all of them, in index order
+    int n_eq = 0;
+#pragma unroll
+    for (int i = 0; i < IPT; ++i) n_eq += (cand[i] && !all && !none && key[i] == tkey) ? 1 : 0;
+    int total_eq;
+    int eq_rank = block_excl_scan(n_eq, scan_lds, &total_eq);
+
+    bool kept[IPT];
+    int n_kept = 0;
+#pragma unroll
+    for (int i = 0; i < IPT; ++i) {
+        const int t = t0 + i;
+        bool kflag;
+        if (t >= n)
+            kflag = false;
+        else if (all || t < forced)
+            kflag = true;
+        else if (none)
+            kflag = false;
+        else if (key[i] < tkey)
+            kflag = true;
+        else if (key[i] == tkey)
+            kflag = eq_rank++ < k_eq;
+        else
+            kflag = false;
+        kept[i] = kflag;
+        n_kept += kflag ? 1 : 0;
+    }
+    int total_kept;
+    int pos = block_excl_scan(n_kept, scan_lds, &total_kept);
+#pragma unroll
+    for (int i = 0; i < IPT; ++i) {
+        const int t = t0 + i;
+        if (t < n) kp[t] = kept[i] ? 1 : 0;
+        if (kept[i]) {
+            if (pos < m) out[pos] = t;
+            ++pos;
+        }
+    }
+}
+
 __global__ void mask_from_idx_kernel(const int32_t* __restrict__ kept_idx, int n, int m,
                                      uint8_t* __restrict__ keep)
 {
@@ -215,7 +332,7 @@ hipError_t launch_fuse(const Dims& d, int fusion, const float* sim_k, const floa
 {
     const size_t lds = (size_t)2 * d.Hkv * kFuseTokens * sizeof(float);
     dim3 grid((d.n + kFuseTokens - 1) / kFuseTokens, d.B);
-    fuse_kernel<<<grid, dim3(kFuseTokens), lds, s>>>(sim_k, sim_v, d.Hkv, d.n, fusion, fused);
+    fuse_kernel<<<grid, dim3(kFuseThreads), lds, s>>>(sim_k, sim_v, d.Hkv, d.n, fusion, fused);
     return hipGetLastError();
 }
 
@@ -223,6 +340,24 @@ hipError_t launch_select(const Dims& d, int warmup, const float* fused, uint8_t*
                          float* tau, hipStream_t s)
 {
     select_kernel<<<dim3(d.B), dim3(kSelThreads), 0, s>>>(fused, d.n, d.m, warmup, keep, tau);
+    return hipGetLastError();
+}
+
+hipError_t launch_select_compact(const Dims& d, int warmup, const float* fused, uint8_t* keep,
+                                 int32_t* kept_idx, float* tau, hipStream_t s)
+{
+    const int ipt = (d.n + kSelThreads - 1) / kSelThreads;
+    if (ipt <= 4)
+        select_compact_kernel<4><<<dim3(d.B), dim3(kSelThreads), 0, s>>>(fused, d.n, d.m, warmup, keep, kept_idx, tau);
+    else if (ipt <= 8)
+        select_compact_kernel<8><<<dim3(d.B), dim3(kSelThreads), 0, s>>>(fused, d.n, d.m, warmup, keep, kept_idx, tau);
+    else if (ipt <= 32)
+        select_compact_kernel<32><<<dim3(d.B), dim3(kSelThreads), 0, s>>>(fused, d.n, d.m, warmup, keep, kept_idx, tau);
+    else {
+        // longer rows: scores stay in global memory, decision and compaction in two launches
+        select_kernel<<<dim3(d.B), dim3(kSelThreads), 0, s>>>(fused, d.n, d.m, warmup, keep, tau);
+        compact_kernel<<<dim3(d.B), dim3(kSelThreads), 0, s>>>(keep, d.n, d.m, kept_idx);
+    }
     return hipGetLastError();
 }
 

@@ -37,6 +37,10 @@ hipError_t launch_fuse(const Dims& d, int fusion, const float* sim_k, const floa
 hipError_t launch_select(const Dims& d, int warmup, const float* fused, uint8_t* keep,
                          float* tau, hipStream_t s);
 hipError_t launch_compact(const Dims& d, const uint8_t* keep, int32_t* kept_idx, hipStream_t s);
+// decision and compaction in one launch (rows of up to 32768 tokens; longer rows take the two
+// kernels above)
+hipError_t launch_select_compact(const Dims& d, int warmup, const float* fused, uint8_t* keep,
+                                 int32_t* kept_idx, float* tau, hipStream_t s);
 // keep mask from an index list (for callers that bring their own kept set)
 hipError_t launch_mask_from_idx(const Dims& d, const int32_t* kept_idx, uint8_t* keep,
                                 hipStream_t s);

@@ -227,9 +227,8 @@ tf_status tf_select(tf_ctx* ctx, const tf_params* p, const float* fused, uint8_t
     if (!fused || !keep || !kept_idx) return fail(ctx, TF_ERR_INVALID_ARG, "fused, keep and kept_idx must not be NULL");
     const tf::Dims d = make_dims(p, tf_keep_count(p->seq, p->prune_ratio));
     hipStream_t s = (hipStream_t)stream;
-    st = dev(ctx, tf::launch_select(d, p->warmup, fused, keep, tau, s), "select launch");
-    if (st != TF_OK) return st;
-    return dev(ctx, tf::launch_compact(d, keep, kept_idx, s), "compact launch");
+    return dev(ctx, tf::launch_select_compact(d, p->warmup, fused, keep, kept_idx, tau, s),
+               "select launch");
 }
 
 tf_status tf_attend(tf_ctx* ctx, const tf_params* p, const void* Q, const void* K, const void* V,
@@ -278,11 +277,10 @@ tf_status tf_filtered_attention(tf_ctx* ctx, const tf_params* p, const void* Q, 
     st = dev(ctx, tf::launch_fuse(d, p->fusion, sk, sv, fused, s), "fuse launch");
     if (st != TF_OK) return st;
     mark(ctx, slot, 2, s);
-    st = dev(ctx, tf::launch_select(d, p->warmup, fused, keep, tau, s), "select launch");
+    st = dev(ctx, tf::launch_select_compact(d, p->warmup, fused, keep, kept_idx, tau, s),
+             "select launch");
     if (st != TF_OK) return st;
-    mark(ctx, slot, 3, s);
-    st = dev(ctx, tf::launch_compact(d, keep, kept_idx, s), "compact launch");
-    if (st != TF_OK) return st;
+    mark(ctx, slot, 3, s);  // compaction is part of the decision kernel
     mark(ctx, slot, 4, s);
     st = run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, s, slot);
     if (st != TF_OK) return st;

@@ -141,7 +141,8 @@ def test_score_degenerate_inputs(ctx):
 @pytest.mark.parametrize("case", [(1, 512, 0.5, 1), (3, 1000, 0.25, 1), (2, 4096, 0.5, 4),
                                   (1, 33, 0.9, 1), (2, 17, 0.0, 1), (1, 40, 0.5, 0),
                                   (1, 12, 0.8, 5), (1, 1, 0.5, 1), (1, 5000, 0.999, 1),
-                                  (1, 32768, 0.5, 1)])
+                                  (1, 32768, 0.5, 1), (2, 5000, 0.5, 3), (1, 8192, 0.3, 1),
+                                  (1, 40000, 0.5, 1), (2, 33000, 0.75, 2)])
 def test_select_bit_exact_on_identical_scores(ctx, case):
     """Same float scores in, so the decision must agree bit for bit, ties included."""
     Bn, n, r, W = case
