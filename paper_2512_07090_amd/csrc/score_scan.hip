@@ -42,6 +42,17 @@ struct Row8<uint16_t> {             // bf16 storage
             x[2 * i + 1] = __builtin_bit_cast(float, w[i] & 0xffff0000u);
         }
     }
+    // sum of squares of the 8 elements: two exact bf16 products per v_dot2c_f32_bf16
+    __device__ __forceinline__ float sumsq() const
+    {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        float s = 0.f;
+        s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, raw.x), __builtin_bit_cast(bf16x2, raw.x), s, false);
+        s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, raw.y), __builtin_bit_cast(bf16x2, raw.y), s, false);
+        s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, raw.z), __builtin_bit_cast(bf16x2, raw.z), s, false);
+        s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, raw.w), __builtin_bit_cast(bf16x2, raw.w), s, false);
+        return s;
+    }
 };
 
 template <>
@@ -57,6 +68,13 @@ struct Row8<float> {
     {
         x[0] = lo.x; x[1] = lo.y; x[2] = lo.z; x[3] = lo.w;
         x[4] = hi.x; x[5] = hi.y; x[6] = hi.z; x[7] = hi.w;
+    }
+    __device__ __forceinline__ float sumsq() const
+    {
+        float s = lo.x * lo.x;
+        s = fmaf(lo.y, lo.y, s); s = fmaf(lo.z, lo.z, s); s = fmaf(lo.w, lo.w, s);
+        s = fmaf(hi.x, hi.x, s); s = fmaf(hi.y, hi.y, s); s = fmaf(hi.z, hi.z, s);
+        return fmaf(hi.w, hi.w, s);
     }
 };
 
@@ -128,7 +146,7 @@ __global__ __launch_bounds__(kThreads) void scan_score_kernel(
     const int tid = threadIdx.x;
     const int l = tid & 15;          // column slice: columns 8l .. 8l+7
     const int rg = tid >> 4;         // row group in the tile: rows 8rg .. 8rg+7
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int rgw = (tid >> 4) & 3;  // row group inside the wave
 
     const int t_begin = seg * seg_len;
@@ -149,7 +167,7 @@ __global__ __launch_bounds__(kThreads) void scan_score_kernel(
     load_tile(buf0, X, s_t, t_begin + rg * kR, t_end, 8 * l);
 
     int parity = 0;
-    auto process = [&](const Row8<T>* rows, int t0) {
+    auto process = [&](const Row8<T>* rows, int t0, bool first_tile) {
         float x[kR][8];
         float tot[8];
 #pragma unroll
@@ -199,22 +217,30 @@ __global__ __launch_bounds__(kThreads) void scan_score_kernel(
         }
         parity ^= 1;
 
-        // replay the 8 rows against the running prefix; lane r of the DPP row keeps row r
+        // replay the 8 rows against the running prefix; lane r of the DPP row keeps row r.
+        // |A|^2 is taken directly for the thread's first row and then advanced with
+        // |A + x|^2 = |A|^2 + 2 <A, x> + |x|^2 from the two reductions that are needed anyway.
+        // The chain's first tile takes it directly for every row: there the prefix is a sum of
+        // few rows and may cancel.
         float my_dot = 0.f, my_aa = 0.f, my_xx = 0.f;
+        float aa_run = 0.f;
 #pragma unroll
         for (int r = 0; r < kR; ++r) {
-            float dot = 0.f, aa = 0.f, xx = 0.f;
+            float dot = 0.f;
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                dot = fmaf(A[c], x[r][c], dot);
-                aa = fmaf(A[c], A[c], aa);
-                xx = fmaf(x[r][c], x[r][c], xx);
-                A[c] += x[r][c];
+            for (int c = 0; c < 8; ++c) dot = fmaf(A[c], x[r][c], dot);
+            if (r == 0 || first_tile) {
+                float aa = 0.f;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) aa = fmaf(A[c], A[c], aa);
+                aa_run = row16_sum(aa);
             }
+#pragma unroll
+            for (int c = 0; c < 8; ++c) A[c] += x[r][c];
             dot = row16_sum(dot);
-            aa = row16_sum(aa);
-            xx = row16_sum(xx);
-            if (l == r) { my_dot = dot; my_aa = aa; my_xx = xx; }
+            const float xx = row16_sum(rows[r].sumsq());
+            if (l == r) { my_dot = dot; my_aa = aa_run; my_xx = xx; }
+            aa_run = fmaf(2.f, dot, aa_run + xx);
         }
         if (l < kR) {
             const int t = t0 + rg * kR + l;
@@ -233,10 +259,10 @@ __global__ __launch_bounds__(kThreads) void scan_score_kernel(
     for (int t0 = t_begin; t0 < t_end; t0 += 2 * kTile) {
         const bool more1 = t0 + kTile < t_end;
         if (more1) load_tile(buf1, X, s_t, t0 + kTile + rg * kR, t_end, 8 * l);
-        process(buf0, t0);
+        process(buf0, t0, t0 == 0);
         if (!more1) break;
         if (t0 + 2 * kTile < t_end) load_tile(buf0, X, s_t, t0 + 2 * kTile + rg * kR, t_end, 8 * l);
-        process(buf1, t0 + kTile);
+        process(buf1, t0 + kTile, false);
     }
 }
 
