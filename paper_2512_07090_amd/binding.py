@@ -13,7 +13,8 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libtokfilt.so")
+# TOKFILT_LIB names another build of the same library (e.g. a kernel variant under test)
+LIB_PATH = os.environ.get("TOKFILT_LIB") or os.path.join(_HERE, "libtokfilt.so")
 
 TF_OK, TF_ERR_INVALID_ARG, TF_ERR_UNSUPPORTED, TF_ERR_WORKSPACE_TOO_SMALL, TF_ERR_DEVICE = range(5)
 TF_F32, TF_BF16 = 0, 1

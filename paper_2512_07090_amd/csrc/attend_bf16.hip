@@ -3,7 +3,7 @@
 // queries and keys are the kept tokens, addressed through kept_idx, so "causal" means key rank
 // <= query rank in the compacted order).
 //
-// Flash-style kernel for gfx950.  One workgroup covers 256 kept queries: 8 / U waves, each
+// Flash-style kernel for gfx950.  One work item covers 256 kept queries: 8 / U waves, each
 // owning U sub-tiles of 32 queries (U = 1: two waves per SIMD, 256 registers each; U = 2: one
 // wave per SIMD with the whole register file and half the LDS traffic).  It walks the key tiles
 // (64 kept keys) once, K and V rows gathered through kept_idx into LDS (row-major, two stages
@@ -28,9 +28,12 @@
 //                            ||  read K(h + 2) fragments
 //                 Tiles travel global -> registers -> LDS two iterations ahead of their use
 //                 (two register sets), so an L2 miss has two iterations to arrive.
-//   zero rows     Workgroups past the attention grid write the zero rows of filtered positions
-//                 (they are dispatched last and fill the tail of the launch).
+//   zero rows     The rows of the filtered positions between a query and the next kept token
+//                 are written as zeros together with the query's row (kept_idx is ascending).
+//   scheduling    One persistent workgroup per CU; query tiles are work items taken from
+//                 per-XCD queues (see the kernel).
 #include "tf_kernels.h"
+#include <algorithm>
 
 namespace tf {
 
@@ -48,7 +51,7 @@ constexpr int kVStr = kHeadDim + 32;     // V tile row stride, elements (320 B)
 constexpr int kKTile = kBN * kKStr;      // elements per K tile
 constexpr int kVTile = kBN * kVStr;      // elements per V tile
 constexpr int kOStr = kHeadDim + 8;      // output staging row stride, elements
-constexpr int kZeroRows = 1024;          // positions per zero-fill workgroup
+constexpr int kShortGap = 3;             // zero rows written right after a query's row
 constexpr float kMaxSlack = 8.0f;        // running max may lag the true max by 2^8
 constexpr float kMasked = -1e30f;
 
@@ -112,10 +115,9 @@ __device__ __forceinline__ void store_rows(Rows<4> r, uint16_t* dst, int step)
 
 template <int U>
 __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
-    Dims d, float scale_log2, int n_qt, int attn_blocks, const uint16_t* __restrict__ Q,
+    Dims d, float scale_log2, int n_qt, int cu_per_xcd, const uint16_t* __restrict__ Q,
     const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-    const int32_t* __restrict__ kept_idx, const uint8_t* __restrict__ keep,
-    uint16_t* __restrict__ O)
+    const int32_t* __restrict__ kept_idx, uint16_t* __restrict__ O, unsigned* __restrict__ queue)
 {
     constexpr int NT = 512 / U;    // threads
     constexpr int CH = 1024 / NT;  // 16-byte chunks per thread per tensor per tile
@@ -125,31 +127,60 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
     uint16_t* const v_lds = smem + 2 * kKTile;  // 2 stages of V
     static_assert(kBM * kOStr <= 2 * kKTile + 2 * kVTile, "output staging must fit");
 
+    __shared__ int s_item[2];
     const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: branches on it are scalar
 
-    // ---- zero rows of filtered positions (blocks after the attention grid) ----------------
-    if ((int)blockIdx.x >= attn_blocks) {
-        const int z = blockIdx.x - attn_blocks;
-        const int n_zb = (d.n + kZeroRows - 1) / kZeroRows;
-        const int zbh = z / n_zb;
-        const int p0 = (z % n_zb) * kZeroRows;
-        const int p1 = min(p0 + kZeroRows, d.n);
-        uint16_t* Oz = O + (long long)(zbh / d.Hq) * d.os[0] + (long long)(zbh % d.Hq) * d.os[1];
-        const uint8_t* kp = keep + (long long)(zbh / d.Hq) * d.n;
-        const uint4 zero = make_uint4(0, 0, 0, 0);
-        for (int p = p0 + (tid >> 4); p < p1; p += NT / 16)
-            if (!kp[p]) *reinterpret_cast<uint4*>(Oz + (long long)p * d.os[2] + 8 * (tid & 15)) = zero;
-        return;
+    // Persistent workgroups (one per CU) take work items from eight queues, one per XCD: the
+    // hardware dispatcher hands out workgroups in order, which leaves CUs idle for many
+    // microseconds whenever durations differ as much as those of causal query tiles do.
+    // The (batch, head) groups are split into eight contiguous runs, so an XCD's L2 holds the K
+    // and V of the few groups it is working on.  Order inside a queue: first the long query
+    // tiles, a handful of groups at a time, longest first; then the short query tiles of the
+    // whole run, longest first, so that what is left for the end is fine-grained and the CUs
+    // finish together.  A workgroup whose own queue is empty takes
+    // from the next one; the counters only grow, so every workgroup reaches the end of all
+    // eight and exits.
+    const int n_groups = d.B * d.Hq;
+    const int my_xcd = __builtin_amdgcn_s_getreg((31 << 11) | 20) & 7;  // XCC_ID
+    auto pop = [&]() -> int {
+        for (int k = 0; k < 8; ++k) {
+            const int x = (my_xcd + k) & 7;
+            const int ng = (x + 1) * n_groups / 8 - x * n_groups / 8;
+            const unsigned total = (unsigned)ng * (unsigned)n_qt;
+            if (total == 0) continue;
+            const unsigned i = atomicAdd(&queue[x], 1u);
+            if (i < total) return (x << 27) | (int)i;
+        }
+        return -1;
+    };
+    if (tid == 0) s_item[0] = pop();
+    __syncthreads();
+
+    for (int it = 0;; ++it) {
+    const int item = __builtin_amdgcn_readfirstlane(s_item[it & 1]);
+    if (item < 0) break;
+    if (tid == 0) s_item[(it + 1) & 1] = pop();  // the next item, fetched while this one runs
+    const int x = item >> 27, pos = item & ((1 << 27) - 1);
+    const int g_lo = x * n_groups / 8;
+    const int ng = (x + 1) * n_groups / 8 - g_lo;
+    const int qi = pos;
+    const int n_short = (3 * n_qt) >> 3;  // query tiles 0 .. n_short - 1 are left for the end
+    const int n_long = n_qt - n_short;
+    int qt, bh;
+    if (qi < ng * n_long) {
+        const int chunk_sz = max(1, cu_per_xcd / n_qt);  // groups in flight on one XCD
+        const int chunk = qi / (chunk_sz * n_long);
+        const int cs = min(chunk_sz, ng - chunk * chunk_sz);
+        const int r = qi - chunk * chunk_sz * n_long;
+        qt = n_qt - 1 - r / cs;
+        bh = g_lo + chunk * chunk_sz + r % cs;
+    } else {
+        const int r = qi - ng * n_long;
+        qt = n_short - 1 - r / ng;
+        bh = g_lo + r % ng;
     }
-
-    // Workgroup ids are dealt round-robin to the 8 XCDs; renumber so that each XCD gets a
-    // contiguous run of (batch, head) groups (its L2 then holds that group's K and V), and
-    // inside a group start with the last, longest query tile.
-    const int per_xcd = attn_blocks >> 3;
-    const int logical = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    const int bh = logical / n_qt;
-    if (bh >= d.B * d.Hq) return;
-    const int qt = n_qt - 1 - logical % n_qt;
     const int b = bh / d.Hq, hq = bh % d.Hq;
     const int hk = hq / (d.Hq / d.Hkv);
 
@@ -160,7 +191,6 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
     uint16_t* Ob = O + (long long)b * d.os[0] + (long long)hq * d.os[1];
     const long long s_t = d.kvs[2];
 
-    const int lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, hh = lane >> 5;
 
     const int i0 = qt * kBM;
@@ -192,9 +222,15 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
 #define TF_COPY_POS(DST, SRC) DST = SRC
 
     // ---- prologue, part 1: every index first, then every row load, no wait in between -----
-    int qpos[U];  // positions of this lane's queries
+    int qpos[U];   // positions of this lane's queries
+    int qnext[U];  // position of the next kept token (n after the last one): rows in between
+                   // belong to filtered tokens and are written as zeros with the query's row
 #pragma unroll
-    for (int u = 0; u < U; ++u) qpos[u] = idx[lim[u]];
+    for (int u = 0; u < U; ++u) {
+        qpos[u] = idx[lim[u]];
+        const int nx = idx[min(lim[u] + 1, m_last)];
+        qnext[u] = lim[u] < m_last ? nx : d.n;
+    }
     Pos<CH> pos_0, pos_1;
     TF_LOAD_IDX(pos_0, 0);
     TF_LOAD_IDX(pos_1, kBN);
@@ -281,7 +317,10 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
         float mx = fmaxf(sacc[0], sacc[1]);
 #pragma unroll
         for (int v = 2; v < 16; v += 2) mx = fmaxf(mx, fmaxf(sacc[v], sacc[v + 1]));
-        return fmaxf(mx, __shfl_xor(mx, 32));
+        // the other half of this query's keys sits 32 lanes away: swap halves in the VALU
+        const unsigned mb = __builtin_bit_cast(unsigned, mx);
+        const auto sw = __builtin_amdgcn_permlane32_swap(mb, mb, false, false);
+        return fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
     };
     // Move a running max when the new max exceeds it by more than the slack; rescale what
     // has been accumulated so far for that sub-tile.
@@ -310,13 +349,13 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
         TF_QK(S_NXT);                                                                          \
         _Pragma("unroll") for (int u = 0; u < U; ++u) {                                        \
             const float mc = m_run[u] * scale_log2;                                            \
-            float psum = 0.f;                                                                  \
+            float ps_[4] = {0.f, 0.f, 0.f, 0.f};                                               \
             _Pragma("unroll") for (int v = 0; v < 16; ++v) {                                   \
                 const float p = __builtin_amdgcn_exp2f(fmaf(S_CUR[u][v], scale_log2, -mc));    \
-                psum += p;                                                                     \
+                ps_[v & 3] += p;                                                               \
                 pf[u][v >> 3][v & 7] = (__bf16)p;                                              \
             }                                                                                  \
-            l_run[u] += psum;                                                                  \
+            l_run[u] += (ps_[0] + ps_[1]) + (ps_[2] + ps_[3]);                                 \
         }                                                                                      \
         /* block 2 */                                                                          \
         read_kf(KS_NEXT);                                                                      \
@@ -399,32 +438,60 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
             }
     }
     __syncthreads();
+    // Every 16-lane group writes one query's row and, after it, the zero rows of the filtered
+    // positions up to the next kept token (the first kShortGap of them; longer gaps below).
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+    uint16_t* const Oc = Ob + 8 * (lane & 15);  // this lane's 16-byte column
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
             const int r = 4 * it + (lane >> 4);  // query row inside the sub-tile
             const int p = __shfl(qpos[u], r);    // its position, held by lane r
+            const int pn = __shfl(qnext[u], r);
             if (iw + 32 * u + r < d.m) {
                 const uint4 v = *reinterpret_cast<const uint4*>(os + (32 * u + r) * kOStr + 8 * (lane & 15));
-                *reinterpret_cast<uint4*>(Ob + (long long)p * d.os[2] + 8 * (lane & 15)) = v;
+                *reinterpret_cast<uint4*>(Oc + (long long)p * d.os[2]) = v;
+                const int g_end = min(pn, p + 1 + kShortGap);
+                for (int g = p + 1; g < g_end; ++g) *reinterpret_cast<uint4*>(Oc + (long long)g * d.os[2]) = zero4;
             }
         }
+    // long gaps, one at a time, four rows per store instruction
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int z0 = qpos[u] + 1 + kShortGap;
+        unsigned long long todo = __ballot(lane < 32 && iw + 32 * u + lane < d.m && z0 < qnext[u]);
+        while (todo) {
+            const int r = __builtin_ctzll(todo);
+            todo &= todo - 1;
+            const int ze = __shfl(qnext[u], r);
+            for (int g = __shfl(z0, r) + (lane >> 4); g < ze; g += 4)
+                *reinterpret_cast<uint4*>(Oc + (long long)g * d.os[2]) = zero4;
+        }
+    }
+    // positions before the first kept token
+    if (qt == 0 && blk == 0) {
+        const int ze = __shfl(qpos[0], 0);
+        for (int g = lane >> 4; g < ze; g += 4) *reinterpret_cast<uint4*>(Oc + (long long)g * d.os[2]) = zero4;
+    }
+    __syncthreads();  // the staging area becomes tile stages again
+    }  // items
 }
 
 }  // namespace
 
 hipError_t launch_attend_bf16(const Dims& d, float scale, const void* Q, const void* K,
-                              const void* V, const int32_t* kept_idx, const uint8_t* keep, void* O,
-                              hipStream_t s)
+                              const void* V, const int32_t* kept_idx, void* O, unsigned* queue,
+                              int n_cu, hipStream_t s)
 {
     constexpr int U = 1;
     const int n_qt = (d.m + kBM - 1) / kBM;
-    const int attn = (n_qt * d.Hq * d.B + 7) & ~7;
-    const int zero = d.m < d.n ? d.B * d.Hq * ((d.n + kZeroRows - 1) / kZeroRows) : 0;
-    attend_bf16_kernel<U><<<dim3(attn + zero), dim3(512 / U), 0, s>>>(
-        d, scale * 1.44269504088896340736f, n_qt, attn, (const uint16_t*)Q, (const uint16_t*)K,
-        (const uint16_t*)V, kept_idx, keep, (uint16_t*)O);
+    const long long items = (long long)d.B * d.Hq * n_qt;
+    if (items >= (1ll << 27)) return hipErrorInvalidValue;  // a queue position takes 27 bits
+    const int grid = (int)std::min<long long>(items, std::max(n_cu, 1));
+    attend_bf16_kernel<U><<<dim3(grid), dim3(512 / U), 0, s>>>(
+        d, scale * 1.44269504088896340736f, n_qt, std::max(n_cu / 8, 1), (const uint16_t*)Q,
+        (const uint16_t*)K, (const uint16_t*)V, kept_idx, (uint16_t*)O, queue);
     return hipGetLastError();
 }
 

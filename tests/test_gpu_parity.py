@@ -206,6 +206,40 @@ def test_attend_softmax_scale_and_single_kept(ctx):
     assert np.abs(buf.O.float().cpu().numpy() - ref).max() <= 2e-2
 
 
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_attend_zero_rows_with_long_gaps(ctx, dt):
+    """Kept sets with filtered runs of every length (before the first kept token, between kept
+    tokens across query-tile borders, after the last one): every filtered row must come back
+    as zeros and every kept row must match, on an output buffer poisoned with NaN."""
+    _say("attend long gaps %s" % dt)
+    n = 3000
+    q, k, v, _ = synth.make_random_qkv(2, 4, 2, n, 128, dtype=dt, seed=31)
+    rng = np.random.default_rng(5)
+    rows = []
+    for first, last in ((37, 2400), (0, n - 1)):
+        mask = np.zeros(n, dtype=bool)
+        mask[first:last + 1] = rng.random(last + 1 - first) < 0.6
+        mask[first] = mask[last] = True
+        for lo, ln in ((100, 1), (300, 2), (500, 3), (520, 4), (600, 5), (700, 9), (1000, 300), (1500, 257)):
+            mask[lo:lo + ln] = False          # runs of exactly these lengths (if not longer)
+            mask[lo - 1] = mask[lo + ln] = True
+        rows.append(np.flatnonzero(mask))
+    m = min(len(r) for r in rows)
+    idx = np.stack([r[:m] for r in rows]).astype(np.int32)
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.5)
+    buf = B.Buffers(p, "cuda:0")
+    buf.O.fill_(float("nan"))
+    ctx.tf_attend(p, q.cuda(), k.cuda(), v.cuda(), torch.from_numpy(idx).cuda(), m, buf.O, buf.ws)
+    torch.cuda.synchronize()
+    O_g = buf.O.float().cpu().numpy().astype(np.float64)
+    assert not np.isnan(O_g).any()
+    ref = oracle.attend(q, k, v, idx)
+    for b in range(2):
+        filtered = np.setdiff1d(np.arange(n), idx[b])
+        assert np.all(O_g[b][:, filtered] == 0)
+    assert np.abs(O_g - ref).max() <= ATTN_TOL[q.dtype]
+
+
 # ------------------------------------------------------------------ whole path
 
 def test_whole_path_workload_1_fp32(ctx):
