@@ -422,6 +422,10 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
 #undef TF_COPY_POS
 
     // normalise, transpose through LDS (all tiles are consumed) and write whole rows
+    // (the lane number goes through an opaque move so that the addresses below are formed
+    // here, per item, instead of being carried in registers across the tile loop)
+    int ln = lane;
+    asm volatile("" : "+v"(ln));
     uint16_t* os = smem + wave * (WQ * kOStr);  // [WQ queries][kOStr]
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -434,23 +438,23 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
                 bf16x4 o4;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o4[e] = (__bf16)(oacc[u][dt][4 * v4 + e] * inv);
-                *reinterpret_cast<bf16x4*>(os + (32 * u + col) * kOStr + 32 * dt + 8 * v4 + 4 * hh) = o4;
+                *reinterpret_cast<bf16x4*>(os + (32 * u + (ln & 31)) * kOStr + 32 * dt + 8 * v4 + 4 * (ln >> 5)) = o4;
             }
     }
     __syncthreads();
     // Every 16-lane group writes one query's row and, after it, the zero rows of the filtered
     // positions up to the next kept token (the first kShortGap of them; longer gaps below).
     const uint4 zero4 = make_uint4(0, 0, 0, 0);
-    uint16_t* const Oc = Ob + 8 * (lane & 15);  // this lane's 16-byte column
+    uint16_t* const Oc = Ob + 8 * (ln & 15);  // this lane's 16-byte column
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int it = 0; it < 8; ++it) {
-            const int r = 4 * it + (lane >> 4);  // query row inside the sub-tile
+            const int r = 4 * it + (ln >> 4);  // query row inside the sub-tile
             const int p = __shfl(qpos[u], r);    // its position, held by lane r
             const int pn = __shfl(qnext[u], r);
             if (iw + 32 * u + r < d.m) {
-                const uint4 v = *reinterpret_cast<const uint4*>(os + (32 * u + r) * kOStr + 8 * (lane & 15));
+                const uint4 v = *reinterpret_cast<const uint4*>(os + (32 * u + r) * kOStr + 8 * (ln & 15));
                 *reinterpret_cast<uint4*>(Oc + (long long)p * d.os[2]) = v;
                 const int g_end = min(pn, p + 1 + kShortGap);
                 for (int g = p + 1; g < g_end; ++g) *reinterpret_cast<uint4*>(Oc + (long long)g * d.os[2]) = zero4;
@@ -460,19 +464,19 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int z0 = qpos[u] + 1 + kShortGap;
-        unsigned long long todo = __ballot(lane < 32 && iw + 32 * u + lane < d.m && z0 < qnext[u]);
+        unsigned long long todo = __ballot(ln < 32 && iw + 32 * u + ln < d.m && z0 < qnext[u]);
         while (todo) {
             const int r = __builtin_ctzll(todo);
             todo &= todo - 1;
             const int ze = __shfl(qnext[u], r);
-            for (int g = __shfl(z0, r) + (lane >> 4); g < ze; g += 4)
+            for (int g = __shfl(z0, r) + (ln >> 4); g < ze; g += 4)
                 *reinterpret_cast<uint4*>(Oc + (long long)g * d.os[2]) = zero4;
         }
     }
     // positions before the first kept token
     if (qt == 0 && blk == 0) {
         const int ze = __shfl(qpos[0], 0);
-        for (int g = lane >> 4; g < ze; g += 4) *reinterpret_cast<uint4*>(Oc + (long long)g * d.os[2]) = zero4;
+        for (int g = ln >> 4; g < ze; g += 4) *reinterpret_cast<uint4*>(Oc + (long long)g * d.os[2]) = zero4;
     }
     __syncthreads();  // the staging area becomes tile stages again
     }  // items
