@@ -223,19 +223,19 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
 
     // ---- prologue, part 1: every index first, then every row load, no wait in between -----
     int qpos[U];   // positions of this lane's queries
-    int qnext[U];  // position of the next kept token (n after the last one): rows in between
-                   // belong to filtered tokens and are written as zeros with the query's row
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        qpos[u] = idx[lim[u]];
-        const int nx = idx[min(lim[u] + 1, m_last)];
-        qnext[u] = lim[u] < m_last ? nx : d.n;
-    }
+    for (int u = 0; u < U; ++u) qpos[u] = idx[lim[u]];
     Pos<CH> pos_0, pos_1;
-    TF_LOAD_IDX(pos_0, 0);
-    TF_LOAD_IDX(pos_1, kBN);
-    TF_LOAD_IDX(pos_v, 2 * kBN);
-    TF_LOAD_IDX(pos_k, 3 * kBN);
+    {
+        // (opaque copy of the row number: these four index sets do not depend on the item, and
+        // would otherwise be kept in registers, or spilled, across the whole item loop)
+        int row0p = row0;
+        asm volatile("" : "+v"(row0p));
+        pos_0 = load_pos(idx, row0p, RS, m_last, (Pos<CH>*)nullptr);
+        pos_1 = load_pos(idx, kBN + row0p, RS, m_last, (Pos<CH>*)nullptr);
+        pos_v = load_pos(idx, 2 * kBN + row0p, RS, m_last, (Pos<CH>*)nullptr);
+        pos_k = load_pos(idx, 3 * kBN + row0p, RS, m_last, (Pos<CH>*)nullptr);
+    }
     // Q fragments (B operand of S^T = K Q^T): for sub-tile u, lane (col, hh) holds, for
     // k-step s, the 8 elements 16 s + 8 hh .. +7 of query row iw + 32 u + col.
     bf16x8 qf[U][8];
@@ -426,6 +426,14 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
     // here, per item, instead of being carried in registers across the tile loop)
     int ln = lane;
     asm volatile("" : "+v"(ln));
+    // position of the next kept token after each query (n after the last one): the rows in
+    // between belong to filtered tokens and are written as zeros with the query's row
+    int qnext[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int nx = idx[min(lim[u] + 1, m_last)];
+        qnext[u] = lim[u] < m_last ? nx : d.n;
+    }
     uint16_t* os = smem + wave * (WQ * kOStr);  // [WQ queries][kOStr]
 #pragma unroll
     for (int u = 0; u < U; ++u) {
