@@ -12,7 +12,11 @@ Prints ONE JSON line.  Besides the whole-path throughput it carries
                 the launch stream inside the timed steps, against the 2.5 PFLOP/s dense bf16
                 peak;
   cpu_baseline  the CPU oracle, as it stands, timed on the host cores over a bounded sample
-                (whole path on one batch row of the same workload).
+                (whole path on one batch row of the same workload);
+  ceilings      what this device reaches on a plain streaming read of the K tensor and on
+                back-to-back bf16 MFMAs (the library's probes), next to the vendor peaks;
+  other_ratios  the same workload at the other pruning ratio its configuration names (0.25),
+                timed the same way (context: `value` is the 50 % line).
 """
 from __future__ import annotations
 
@@ -135,12 +139,42 @@ def main():
                       "traffic": read_traffic("scan_score_%s_pmc.txt" % w.name),
                       "avg_kernel_ms": round(stages["score"], 4)}
 
+    # on-box ceilings (measured after the timed region)
+    ceilings = {"hbm_read_GBps": round(ctx.tf_probe_hbm_read(kd), 1),
+                "mfma_bf16_TFLOPs": round(ctx.tf_probe_mfma_bf16(20000), 1),
+                "vendor_hbm_GBps": PEAK_HBM_GBS, "vendor_mfma_bf16_TFLOPs": PEAK_BF16_TFLOPS}
+
+    # the workload's other pruning ratios, timed like the headline
+    other = {}
+    for r2 in w.prune_ratios:
+        if abs(r2 - args.ratio) < 1e-12:
+            continue
+        p2 = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, r2)
+        b2 = B.Buffers(p2, dev)
+
+        def step2():
+            ctx.tf_filtered_attention(p2, qd, kd, vd, b2.keep, b2.kept_idx, b2.fused, b2.tau,
+                                      b2.O, b2.ws)
+        for _ in range(args.warmup):
+            step2()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(K):
+            step2()
+        e1.record()
+        torch.cuda.synchronize()
+        ms2 = e0.elapsed_time(e1) / K
+        fl2 = 2.0 * w.head_dim * b2.m * (b2.m + 1) * w.n_q_heads * w.batch
+        other["%g" % r2] = {"ms_per_step": round(ms2, 4), "tokens_per_s": round(tokens / (ms2 * 1e-3), 1),
+                            "kept_per_row": b2.m, "attn_flops_per_step": fl2}
+        del b2
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle
         # bounded sample: the whole path on the first rows of the same tensors (4 of 8 rows of
         # the default workload: a few seconds on 16 cores)
-        rows = max(1, w.batch // 2)
+        rows = w.batch
         qs, ks, vs = q[:rows], k[:rows], v[:rows]
         t0 = time.perf_counter()
         ref = oracle.filtered_attention(qs, ks, vs, args.ratio)
@@ -164,7 +198,8 @@ def main():
                       "prune_ratio": args.ratio, "kept_per_row": m},
            "roofline": roofline, "cpu_baseline": cpu_baseline,
            "stages_ms": {k_: round(v_, 4) for k_, v_ in stages.items()},
-           "score_roofline": score_roofline, "host_ms_per_step": round(wall_ms, 4)}
+           "score_roofline": score_roofline, "ceilings": ceilings, "other_ratios": other,
+           "host_ms_per_step": round(wall_ms, 4)}
     print(json.dumps(out), flush=True)
 
 

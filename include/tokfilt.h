@@ -146,6 +146,19 @@ tf_status tf_filtered_attention(tf_ctx *ctx, const tf_params *p, const void *Q, 
 tf_status tf_stage_timing_enable(tf_ctx *ctx, int on);
 tf_status tf_stage_timing_read(tf_ctx *ctx, float *ms, int32_t *n_calls);
 
+/* Measurement probes, not part of the path: what this device reaches on the two resources the
+ * path's rooflines are quoted against, to put next to the vendor peaks.  Both enqueue one
+ * warm-up and one timed launch on `stream`, wait for them, and return the rate of the timed
+ * launch.  `sink` is 4 bytes of device memory (never written in practice).
+ * tf_probe_hbm_read: a plain streaming read of `bytes` bytes (a multiple of 16) of device
+ *   memory at `src`, 16-byte aligned; *gb_per_s = bytes / time.
+ * tf_probe_mfma_bf16: `iters` rounds of four independent v_mfma_f32_32x32x16_bf16 per wave, two
+ *   waves per SIMD on every CU; *tflop_per_s = issued flops / time. */
+tf_status tf_probe_hbm_read(tf_ctx *ctx, const void *src, size_t bytes, void *sink, void *stream,
+                            double *gb_per_s);
+tf_status tf_probe_mfma_bf16(tf_ctx *ctx, int32_t iters, void *sink, void *stream,
+                             double *tflop_per_s);
+
 #ifdef __cplusplus
 }
 #endif

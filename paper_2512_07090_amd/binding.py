@@ -24,7 +24,8 @@ STAGE_NAMES = ("score", "fuse", "select", "compact", "zero_rows", "attend")
 
 EXPORTS = ("tf_create", "tf_destroy", "tf_status_string", "tf_last_error", "tf_keep_count",
            "tf_workspace_bytes", "tf_score", "tf_select", "tf_attend", "tf_filtered_attention",
-           "tf_stage_timing_enable", "tf_stage_timing_read")
+           "tf_stage_timing_enable", "tf_stage_timing_read", "tf_probe_hbm_read",
+           "tf_probe_mfma_bf16")
 
 
 class tf_params(ctypes.Structure):
@@ -74,8 +75,11 @@ def lib():
         L.tf_filtered_attention.argtypes = [vp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.tf_stage_timing_enable.argtypes = [vp, ctypes.c_int]
         L.tf_stage_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+        L.tf_probe_hbm_read.argtypes = [vp, vp, sz, vp, vp, ctypes.POINTER(ctypes.c_double)]
+        L.tf_probe_mfma_bf16.argtypes = [vp, i32, vp, vp, ctypes.POINTER(ctypes.c_double)]
         for name in ("tf_score", "tf_select", "tf_attend", "tf_filtered_attention",
-                     "tf_stage_timing_enable", "tf_stage_timing_read"):
+                     "tf_stage_timing_enable", "tf_stage_timing_read", "tf_probe_hbm_read",
+                     "tf_probe_mfma_bf16"):
             getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
@@ -183,6 +187,21 @@ class Context:
         n = ctypes.c_int32()
         self._check(lib().tf_stage_timing_read(self._h, ms, ctypes.byref(n)))
         return [float(x) for x in ms], int(n.value)
+
+
+    def tf_probe_hbm_read(self, src: torch.Tensor, stream=None) -> float:
+        sink = torch.zeros(1, dtype=torch.int32, device=src.device)
+        out = ctypes.c_double()
+        self._check(lib().tf_probe_hbm_read(self._h, _ptr(src), src.numel() * src.element_size(),
+                                            _ptr(sink), _stream(stream), ctypes.byref(out)))
+        return float(out.value)
+
+    def tf_probe_mfma_bf16(self, iters: int, stream=None) -> float:
+        sink = torch.zeros(1, dtype=torch.float32, device="cuda:%d" % self.device)
+        out = ctypes.c_double()
+        self._check(lib().tf_probe_mfma_bf16(self._h, iters, _ptr(sink), _stream(stream),
+                                             ctypes.byref(out)))
+        return float(out.value)
 
 
 class Buffers:

@@ -56,6 +56,11 @@ hipError_t launch_attend_f32(const Dims& d, float scale, const float* Q, const f
 // kAttendQueueWords counters that are zero when the kernel starts; n_cu: compute units of the
 // device (one persistent workgroup each).
 constexpr int kAttendQueueWords = 8;
+
+// ---- measurement probes (not part of the path) ---------------------------------------------
+hipError_t launch_probe_stream_read(const void* src, size_t bytes, void* sink, int n_cu,
+                                    hipStream_t s);
+hipError_t launch_probe_mfma(int iters, void* sink, int n_cu, hipStream_t s);
 hipError_t launch_clear_queue(unsigned* queue, hipStream_t s);
 hipError_t launch_attend_bf16(const Dims& d, float scale, const void* Q, const void* K,
                               const void* V, const int32_t* kept_idx, void* O, unsigned* queue,

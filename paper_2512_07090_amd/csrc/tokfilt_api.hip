@@ -151,6 +151,31 @@ tf_status run_attend(tf_ctx* ctx, const tf_params* p, const tf::Dims& d, const v
 
 }  // namespace
 
+namespace {
+
+// one warm-up and one timed launch of `launch`, milliseconds of the timed one
+template <class F>
+tf_status time_probe(tf_ctx* ctx, hipStream_t s, F launch, float* ms)
+{
+    hipEvent_t e0, e1;
+    if (hipEventCreate(&e0) != hipSuccess) return fail(ctx, TF_ERR_DEVICE, "hipEventCreate failed");
+    if (hipEventCreate(&e1) != hipSuccess) {
+        (void)hipEventDestroy(e0);
+        return fail(ctx, TF_ERR_DEVICE, "hipEventCreate failed");
+    }
+    hipError_t e = launch();
+    if (e == hipSuccess) e = hipEventRecord(e0, s);
+    if (e == hipSuccess) e = launch();
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    if (e == hipSuccess) e = hipEventElapsedTime(ms, e0, e1);
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return dev(ctx, e, "probe");
+}
+
+}  // namespace
+
 extern "C" {
 
 tf_status tf_create(tf_ctx** out, int device)
@@ -333,6 +358,35 @@ tf_status tf_stage_timing_read(tf_ctx* ctx, float* ms, int32_t* n_calls)
     }
     *n_calls = ctx->timing_calls;
     ctx->timing_calls = 0;
+    return TF_OK;
+}
+
+tf_status tf_probe_hbm_read(tf_ctx* ctx, const void* src, size_t bytes, void* sink, void* stream,
+                            double* gb_per_s)
+{
+    if (!ctx) return TF_ERR_INVALID_ARG;
+    if (!src || !sink || !gb_per_s || bytes < 16 || bytes % 16 != 0 || misaligned(src))
+        return fail(ctx, TF_ERR_INVALID_ARG, "src (16-byte aligned), sink, gb_per_s and a positive multiple of 16 bytes are required");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, TF_ERR_DEVICE, "hipSetDevice(%d) failed", ctx->device);
+    hipStream_t s = (hipStream_t)stream;
+    float ms = 0.f;
+    const tf_status st = time_probe(ctx, s, [&] { return tf::launch_probe_stream_read(src, bytes, sink, ctx->n_cu, s); }, &ms);
+    if (st != TF_OK) return st;
+    *gb_per_s = (double)bytes / ((double)ms * 1e-3) / 1e9;
+    return TF_OK;
+}
+
+tf_status tf_probe_mfma_bf16(tf_ctx* ctx, int32_t iters, void* sink, void* stream, double* tflop_per_s)
+{
+    if (!ctx) return TF_ERR_INVALID_ARG;
+    if (!sink || !tflop_per_s || iters < 1) return fail(ctx, TF_ERR_INVALID_ARG, "sink, tflop_per_s and iters >= 1 are required");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, TF_ERR_DEVICE, "hipSetDevice(%d) failed", ctx->device);
+    hipStream_t s = (hipStream_t)stream;
+    float ms = 0.f;
+    const tf_status st = time_probe(ctx, s, [&] { return tf::launch_probe_mfma(iters, sink, ctx->n_cu, s); }, &ms);
+    if (st != TF_OK) return st;
+    const double flops = (double)ctx->n_cu * 8.0 * (double)iters * 4.0 * (2.0 * 32 * 32 * 16);
+    *tflop_per_s = flops / ((double)ms * 1e-3) / 1e12;
     return TF_OK;
 }
 

@@ -390,3 +390,56 @@ def test_full_size_workload_4_gqa(ctx):
 
 def test_full_size_workload_5_long_context_runs(ctx):
     _full_size_case(ctx, synth.workload(4), (0.5,))
+
+
+# ------------------------------------------------------------------ measurement probes
+
+def test_probes_report_plausible_rates(ctx):
+    _say("probes")
+    src = torch.ones(1 << 26, dtype=torch.int32, device="cuda:0")  # 256 MB
+    gbs = ctx.tf_probe_hbm_read(src)
+    tfl = ctx.tf_probe_mfma_bf16(2000)
+    assert 200.0 < gbs < 8000.0 * 1.05, gbs      # below the HBM3E peak, above a PCIe-class rate
+    assert 100.0 < tfl < 2500.0 * 1.05, tfl      # below the dense bf16 MFMA peak
+    with pytest.raises(B.TokfiltError):
+        ctx.tf_probe_mfma_bf16(0)
+
+
+# ------------------------------------------------------------------ stream capture
+
+def test_whole_path_replays_from_a_captured_graph(ctx):
+    """The whole-path call allocates nothing and never synchronises, so it can be captured into
+    a HIP graph.  Every replay (with eager work and synchronisation in between) must reproduce
+    the eager outputs bit for bit."""
+    _say("graph replay")
+    w = synth.scaled(synth.workload(1), batch=2, seq=1500, n_q_heads=8, n_kv_heads=8)
+    q, k, v, _ = synth.make_qkv(w)
+    qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.5)
+    buf = B.Buffers(p, "cuda:0")
+
+    def step():
+        ctx.tf_filtered_attention(p, qd, kd, vd, buf.keep, buf.kept_idx, buf.fused, buf.tau,
+                                  buf.O, buf.ws)
+    step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (buf.keep, buf.kept_idx, buf.fused, buf.tau, buf.O)]
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    for rep in range(3):
+        for t in (buf.keep, buf.kept_idx, buf.fused, buf.tau, buf.O):
+            t.zero_()
+        buf.ws.fill_(0xFF)                       # stale workspace, stale queue counters
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((buf.keep, buf.kept_idx, buf.fused, buf.tau, buf.O), want):
+            assert torch.equal(got, ref), "replay %d differs from the eager result" % rep
+        step()                                   # eager work between replays
+        torch.cuda.synchronize()
