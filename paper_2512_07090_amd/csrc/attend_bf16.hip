@@ -318,9 +318,8 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
 #pragma unroll
         for (int v = 2; v < 16; v += 2) mx = fmaxf(mx, fmaxf(sacc[v], sacc[v + 1]));
         // the other half of this query's keys sits 32 lanes away: swap halves in the VALU
-        const unsigned mb = __builtin_bit_cast(unsigned, mx);
-        const auto sw = __builtin_amdgcn_permlane32_swap(mb, mb, false, false);
-        return fmaxf(__builtin_bit_cast(float, sw[0]), __builtin_bit_cast(float, sw[1]));
+        const FloatPair sw = swap32(mx, mx);
+        return fmaxf(sw.first, sw.second);
     };
     // Move a running max when the new max exceeds it by more than the slack; rescale what
     // has been accumulated so far for that sub-tile.

@@ -84,6 +84,29 @@ __device__ __forceinline__ float row16_sum(float v)
     v += dpp_mov<0x140>(v);  // row_mirror
     return v;
 }
+
+// The gfx950 half swaps, on floats.  With a = (a0 a1 a2 a3) and b = (b0 b1 b2 b3) in 16-lane
+// rows: swap16 returns first = (a0 b0 a2 b2), second = (a1 b1 a3 b3); swap32 returns
+// first = (a0 a1 b0 b1), second = (a2 a3 b2 b3).  Both results go through an opaque move before
+// they are reinterpreted as floats: this compiler's bit cast of the second result silently
+// picks up the first one.
+struct FloatPair { float first, second; };
+__device__ __forceinline__ FloatPair swap16(float a, float b)
+{
+    const auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, a),
+                                                    __builtin_bit_cast(unsigned, b), false, false);
+    unsigned r0 = r[0], r1 = r[1];
+    asm volatile("" : "+v"(r0), "+v"(r1));
+    return FloatPair{__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1)};
+}
+__device__ __forceinline__ FloatPair swap32(float a, float b)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, a),
+                                                    __builtin_bit_cast(unsigned, b), false, false);
+    unsigned r0 = r[0], r1 = r[1];
+    asm volatile("" : "+v"(r0), "+v"(r1));
+    return FloatPair{__builtin_bit_cast(float, r0), __builtin_bit_cast(float, r1)};
+}
 #endif
 
 }  // namespace tf

@@ -207,6 +207,32 @@ def test_attend_softmax_scale_and_single_kept(ctx):
 
 
 @pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_attend_large_logits_in_either_half_of_a_key_block(ctx, dt):
+    """A few keys give logits near 180 (exp overflows fp32 without the running max), placed at
+    every residue of the key rank modulo 8: the row max has to see both halves of the lanes
+    that share a query's keys, whatever the position of the dominant key."""
+    _say("attend large logits %s" % dt)
+    n = 300
+    q, k, v, _ = synth.make_random_qkv(1, 2, 2, n, 128, dtype=dt, seed=77)
+    q = (q.float() * 0.05).to(q.dtype)
+    k = (k.float() * 0.05).to(k.dtype)
+    big = torch.full((128,), 4.0)
+    q[:] = (q.float() + big).to(q.dtype)                 # every query points along `big`
+    for j in (5, 13 + 8, 50 + 3, 77, 130 + 6, 200 + 1, 250 + 7, 280):
+        k[0, :, j] = big.to(k.dtype)                     # logit 16 * 128 / sqrt(128) = 181
+    idx = np.arange(n, dtype=np.int32)[None]
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.0)
+    buf = B.Buffers(p, "cuda:0")
+    buf.O.fill_(float("nan"))
+    ctx.tf_attend(p, q.cuda(), k.cuda(), v.cuda(), torch.from_numpy(idx).cuda(), n, buf.O, buf.ws)
+    torch.cuda.synchronize()
+    O_g = buf.O.float().cpu().numpy().astype(np.float64)
+    assert np.isfinite(O_g).all()
+    ref = oracle.attend(q, k, v, idx)
+    assert np.abs(O_g - ref).max() <= ATTN_TOL[q.dtype]
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
 def test_attend_zero_rows_with_long_gaps(ctx, dt):
     """Kept sets with filtered runs of every length (before the first kept token, between kept
     tokens across query-tile borders, after the last one): every filtered row must come back
