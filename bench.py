@@ -55,6 +55,9 @@ def main():
     ap.add_argument("--workload", type=int, default=1, help="index into the workload table")
     ap.add_argument("--ratio", type=float, default=0.5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="skip the probes and the other pruning ratios (for profiler runs: only "
+                         "the headline configuration's kernels are launched)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run only a plain device copy of known size (to scale HBM counters)")
     args = ap.parse_args()
@@ -140,14 +143,16 @@ def main():
                       "avg_kernel_ms": round(stages["score"], 4)}
 
     # on-box ceilings (measured after the timed region)
-    ceilings = {"hbm_read_GBps": round(ctx.tf_probe_hbm_read(kd), 1),
-                "mfma_bf16_TFLOPs": round(ctx.tf_probe_mfma_bf16(20000), 1),
-                "vendor_hbm_GBps": PEAK_HBM_GBS, "vendor_mfma_bf16_TFLOPs": PEAK_BF16_TFLOPS}
+    ceilings = None
+    if not args.headline_only:
+        ceilings = {"hbm_read_GBps": round(ctx.tf_probe_hbm_read(kd), 1),
+                    "mfma_bf16_TFLOPs": round(ctx.tf_probe_mfma_bf16(20000), 1),
+                    "vendor_hbm_GBps": PEAK_HBM_GBS, "vendor_mfma_bf16_TFLOPs": PEAK_BF16_TFLOPS}
 
     # the workload's other pruning ratios, timed like the headline
     other = {}
     for r2 in w.prune_ratios:
-        if abs(r2 - args.ratio) < 1e-12:
+        if abs(r2 - args.ratio) < 1e-12 or args.headline_only:
             continue
         p2 = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, r2)
         b2 = B.Buffers(p2, dev)

@@ -30,8 +30,8 @@
 //                 (two register sets), so an L2 miss has two iterations to arrive.
 //   zero rows     The rows of the filtered positions between a query and the next kept token
 //                 are written as zeros together with the query's row (kept_idx is ascending).
-//   scheduling    One persistent workgroup per CU; query tiles are work items taken from
-//                 per-XCD queues (see the kernel).
+//   scheduling    One persistent workgroup per CU walks a static list of pairs of query tiles
+//                 (tile p with tile n_qt - 1 - p: equal causal work); see the kernel.
 #include "tf_kernels.h"
 #include <algorithm>
 
@@ -117,7 +117,7 @@ template <int U>
 __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
     Dims d, float scale_log2, int n_qt, int cu_per_xcd, const uint16_t* __restrict__ Q,
     const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-    const int32_t* __restrict__ kept_idx, uint16_t* __restrict__ O, unsigned* __restrict__ queue)
+    const int32_t* __restrict__ kept_idx, uint16_t* __restrict__ O)
 {
     constexpr int NT = 512 / U;    // threads
     constexpr int CH = 1024 / NT;  // 16-byte chunks per thread per tensor per tile
@@ -127,60 +127,34 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
     uint16_t* const v_lds = smem + 2 * kKTile;  // 2 stages of V
     static_assert(kBM * kOStr <= 2 * kKTile + 2 * kVTile, "output staging must fit");
 
-    __shared__ int s_item[2];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: branches on it are scalar
 
-    // Persistent workgroups (one per CU) take work items from eight queues, one per XCD: the
-    // hardware dispatcher hands out workgroups in order, which leaves CUs idle for many
-    // microseconds whenever durations differ as much as those of causal query tiles do.
-    // The (batch, head) groups are split into eight contiguous runs, so an XCD's L2 holds the K
-    // and V of the few groups it is working on.  Order inside a queue: first the long query
-    // tiles, a handful of groups at a time, longest first; then the short query tiles of the
-    // whole run, longest first, so that what is left for the end is fine-grained and the CUs
-    // finish together.  A workgroup whose own queue is empty takes
-    // from the next one; the counters only grow, so every workgroup reaches the end of all
-    // eight and exits.
+    // Persistent workgroups, one per CU, with a static schedule.  (Left to the hardware
+    // dispatcher, one workgroup per query tile, CUs sit idle for many microseconds whenever a
+    // workgroup ends: it hands out workgroups in order, and the durations of causal query tiles
+    // differ by a factor of n_qt.)  The (batch, head) groups are split into eight contiguous
+    // runs, one per XCD, so an XCD's L2 holds the K and V of the few groups it is working on.
     const int n_groups = d.B * d.Hq;
-    const int my_xcd = __builtin_amdgcn_s_getreg((31 << 11) | 20) & 7;  // XCC_ID
-    auto pop = [&]() -> int {
-        for (int k = 0; k < 8; ++k) {
-            const int x = (my_xcd + k) & 7;
-            const int ng = (x + 1) * n_groups / 8 - x * n_groups / 8;
-            const unsigned total = (unsigned)ng * (unsigned)n_qt;
-            if (total == 0) continue;
-            const unsigned i = atomicAdd(&queue[x], 1u);
-            if (i < total) return (x << 27) | (int)i;
-        }
-        return -1;
-    };
-    if (tid == 0) s_item[0] = pop();
-    __syncthreads();
-
-    for (int it = 0;; ++it) {
-    const int item = __builtin_amdgcn_readfirstlane(s_item[it & 1]);
-    if (item < 0) break;
-    if (tid == 0) s_item[(it + 1) & 1] = pop();  // the next item, fetched while this one runs
-    const int x = item >> 27, pos = item & ((1 << 27) - 1);
+    // Static schedule: workgroup j of XCD x (x = id % 8, as the dispatcher deals them) walks
+    // entries j, j + W, ... of the XCD's list of (group, pair of query tiles); a pair joins
+    // query tile p with n_qt - 1 - p, so every entry is the same amount of causal work, and the
+    // workgroups that share a group start on it together and stream the same K / V tiles.
+    const int x = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int nwx = (gridDim.x + 7 - x) >> 3;  // workgroups whose id % 8 is x
     const int g_lo = x * n_groups / 8;
     const int ng = (x + 1) * n_groups / 8 - g_lo;
-    const int qi = pos;
-    const int n_short = (3 * n_qt) >> 3;  // query tiles 0 .. n_short - 1 are left for the end
-    const int n_long = n_qt - n_short;
-    int qt, bh;
-    if (qi < ng * n_long) {
-        const int chunk_sz = max(1, cu_per_xcd / n_qt);  // groups in flight on one XCD
-        const int chunk = qi / (chunk_sz * n_long);
-        const int cs = min(chunk_sz, ng - chunk * chunk_sz);
-        const int r = qi - chunk * chunk_sz * n_long;
-        qt = n_qt - 1 - r / cs;
-        bh = g_lo + chunk * chunk_sz + r % cs;
-    } else {
-        const int r = qi - ng * n_long;
-        qt = n_short - 1 - r / ng;
-        bh = g_lo + r % ng;
-    }
+    const int n_pairs = (n_qt + 1) >> 1;
+    const int n_entries = ng * n_pairs;
+
+    for (int it = 0;; ++it) {
+    const int e = j + (it >> 1) * nwx;
+    if (e >= n_entries) break;
+    const int pr = e % n_pairs;
+    const int bh = g_lo + e / n_pairs;
+    const int qt = (it & 1) ? pr : n_qt - 1 - pr;
+    if ((it & 1) && pr == n_qt - 1 - pr) continue;  // the middle tile of an odd count is alone
     const int b = bh / d.Hq, hq = bh % d.Hq;
     const int hk = hq / (d.Hq / d.Hkv);
 
@@ -492,17 +466,17 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
 }  // namespace
 
 hipError_t launch_attend_bf16(const Dims& d, float scale, const void* Q, const void* K,
-                              const void* V, const int32_t* kept_idx, void* O, unsigned* queue,
-                              int n_cu, hipStream_t s)
+                              const void* V, const int32_t* kept_idx, void* O, int n_cu,
+                              hipStream_t s)
 {
     constexpr int U = 1;
     const int n_qt = (d.m + kBM - 1) / kBM;
     const long long items = (long long)d.B * d.Hq * n_qt;
-    if (items >= (1ll << 27)) return hipErrorInvalidValue;  // a queue position takes 27 bits
-    const int grid = (int)std::min<long long>(items, std::max(n_cu, 1));
+    // at least eight workgroups: every residue of id % 8 owns a share of the groups
+    const int grid = (int)std::max<long long>(8, std::min<long long>(items, std::max(n_cu, 1)));
     attend_bf16_kernel<U><<<dim3(grid), dim3(512 / U), 0, s>>>(
         d, scale * 1.44269504088896340736f, n_qt, std::max(n_cu / 8, 1), (const uint16_t*)Q,
-        (const uint16_t*)K, (const uint16_t*)V, kept_idx, (uint16_t*)O, queue);
+        (const uint16_t*)K, (const uint16_t*)V, kept_idx, (uint16_t*)O);
     return hipGetLastError();
 }
 

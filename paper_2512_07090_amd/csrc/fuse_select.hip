@@ -207,7 +207,7 @@ __global__ __launch_bounds__(kSelThreads) void compact_kernel(const uint8_t* __r
 template <int IPT>
 __global__ __launch_bounds__(kSelThreads) void select_compact_kernel(
     const float* __restrict__ fused, int n, int m, int warmup, uint8_t* __restrict__ keep,
-    int32_t* __restrict__ kept_idx, float* __restrict__ tau, unsigned* __restrict__ queue)
+    int32_t* __restrict__ kept_idx, float* __restrict__ tau)
 {
     __shared__ int hist[256];
     __shared__ int scan_lds[kSelWaves + 1];
@@ -266,7 +266,6 @@ __global__ __launch_bounds__(kSelThreads) void select_compact_kernel(
         k_eq = k;
     }
     if (tid == 0 && tau) tau[b] = all ? INFINITY : (none ? -INFINITY : key2f(tkey));
-    if (queue && b == 0 && tid < kAttendQueueWords) queue[tid] = 0;
 
     // rank of this thread's threshold-equal tokens among all of them, in index order
     int n_eq = 0;
@@ -320,11 +319,10 @@ __global__ void mask_from_idx_kernel(const int32_t* __restrict__ kept_idx, int n
     }
 }
 
-__global__ void clear_bytes_kernel(uint8_t* p, long long count, unsigned* queue)
+__global__ void clear_bytes_kernel(uint8_t* p, long long count)
 {
     const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < count) p[i] = 0;
-    if (queue && i < kAttendQueueWords) queue[i] = 0;
 }
 
 }  // namespace
@@ -346,20 +344,19 @@ hipError_t launch_select(const Dims& d, int warmup, const float* fused, uint8_t*
 }
 
 hipError_t launch_select_compact(const Dims& d, int warmup, const float* fused, uint8_t* keep,
-                                 int32_t* kept_idx, float* tau, unsigned* queue, hipStream_t s)
+                                 int32_t* kept_idx, float* tau, hipStream_t s)
 {
     const int ipt = (d.n + kSelThreads - 1) / kSelThreads;
     if (ipt <= 4)
-        select_compact_kernel<4><<<dim3(d.B), dim3(kSelThreads), 0, s>>>(fused, d.n, d.m, warmup, keep, kept_idx, tau, queue);
+        select_compact_kernel<4><<<dim3(d.B), dim3(kSelThreads), 0, s>>>(fused, d.n, d.m, warmup, keep, kept_idx, tau);
     else if (ipt <= 8)
-        select_compact_kernel<8><<<dim3(d.B), dim3(kSelThreads), 0, s>>>(fused, d.n, d.m, warmup, keep, kept_idx, tau, queue);
+        select_compact_kernel<8><<<dim3(d.B), dim3(kSelThreads), 0, s>>>(fused, d.n, d.m, warmup, keep, kept_idx, tau);
     else if (ipt <= 32)
-        select_compact_kernel<32><<<dim3(d.B), dim3(kSelThreads), 0, s>>>(fused, d.n, d.m, warmup, keep, kept_idx, tau, queue);
+        select_compact_kernel<32><<<dim3(d.B), dim3(kSelThreads), 0, s>>>(fused, d.n, d.m, warmup, keep, kept_idx, tau);
     else {
         // longer rows: scores stay in global memory, decision and compaction in two launches
         select_kernel<<<dim3(d.B), dim3(kSelThreads), 0, s>>>(fused, d.n, d.m, warmup, keep, tau);
         compact_kernel<<<dim3(d.B), dim3(kSelThreads), 0, s>>>(keep, d.n, d.m, kept_idx);
-        if (queue) (void)launch_clear_queue(queue, s);
     }
     return hipGetLastError();
 }
@@ -370,17 +367,11 @@ hipError_t launch_compact(const Dims& d, const uint8_t* keep, int32_t* kept_idx,
     return hipGetLastError();
 }
 
-hipError_t launch_clear_queue(unsigned* queue, hipStream_t s)
-{
-    clear_bytes_kernel<<<dim3(1), dim3(64), 0, s>>>(nullptr, 0, queue);
-    return hipGetLastError();
-}
-
 hipError_t launch_mask_from_idx(const Dims& d, const int32_t* kept_idx, uint8_t* keep,
-                                unsigned* queue, hipStream_t s)
+                                hipStream_t s)
 {
     const long long count = (long long)d.B * d.n;
-    clear_bytes_kernel<<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s>>>(keep, count, queue);
+    clear_bytes_kernel<<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s>>>(keep, count);
     mask_from_idx_kernel<<<dim3((d.m + 255) / 256, d.B), dim3(256), 0, s>>>(kept_idx, d.n, d.m,
                                                                            keep);
     return hipGetLastError();

@@ -39,32 +39,27 @@ hipError_t launch_select(const Dims& d, int warmup, const float* fused, uint8_t*
 hipError_t launch_compact(const Dims& d, const uint8_t* keep, int32_t* kept_idx, hipStream_t s);
 // decision and compaction in one launch (rows of up to 32768 tokens; longer rows take the two
 // kernels above)
-// `queue` (may be null): kAttendQueueWords work-queue counters of the bf16 attention kernel,
-// cleared by this launch so that the attention launch that follows finds them at zero
 hipError_t launch_select_compact(const Dims& d, int warmup, const float* fused, uint8_t* keep,
-                                 int32_t* kept_idx, float* tau, unsigned* queue, hipStream_t s);
+                                 int32_t* kept_idx, float* tau, hipStream_t s);
 // keep mask from an index list (for callers that bring their own kept set)
 hipError_t launch_mask_from_idx(const Dims& d, const int32_t* kept_idx, uint8_t* keep,
-                                unsigned* queue, hipStream_t s);
+                                hipStream_t s);
 
 // ---- attention over the kept tokens -------------------------------------------------------
 hipError_t launch_zero_filtered(const Dims& d, int dtype, const uint8_t* keep, void* O,
                                 hipStream_t s);
 hipError_t launch_attend_f32(const Dims& d, float scale, const float* Q, const float* K,
                              const float* V, const int32_t* kept_idx, float* O, hipStream_t s);
-// also writes the zero rows of filtered positions (kept_idx strictly ascending).  `queue`:
-// kAttendQueueWords counters that are zero when the kernel starts; n_cu: compute units of the
-// device (one persistent workgroup each).
-constexpr int kAttendQueueWords = 8;
+// also writes the zero rows of filtered positions (kept_idx strictly ascending).  n_cu: compute
+// units of the device (one persistent workgroup each).
+hipError_t launch_attend_bf16(const Dims& d, float scale, const void* Q, const void* K,
+                              const void* V, const int32_t* kept_idx, void* O, int n_cu,
+                              hipStream_t s);
 
 // ---- measurement probes (not part of the path) ---------------------------------------------
 hipError_t launch_probe_stream_read(const void* src, size_t bytes, void* sink, int n_cu,
                                     hipStream_t s);
 hipError_t launch_probe_mfma(int iters, void* sink, int n_cu, hipStream_t s);
-hipError_t launch_clear_queue(unsigned* queue, hipStream_t s);
-hipError_t launch_attend_bf16(const Dims& d, float scale, const void* Q, const void* K,
-                              const void* V, const int32_t* kept_idx, void* O, unsigned* queue,
-                              int n_cu, hipStream_t s);
 
 // ---- small device helpers -----------------------------------------------------------------
 #ifdef __HIPCC__

@@ -40,7 +40,7 @@ tf_status fail(tf_ctx* c, tf_status s, const char* fmt, ...)
 size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct Workspace {
-    size_t sim_k, sim_v, seg_tot, keep_tmp, queue, total;  // byte offsets
+    size_t sim_k, sim_v, seg_tot, keep_tmp, total;  // byte offsets
 };
 
 // Pure shape validation, usable without a context.
@@ -97,7 +97,6 @@ Workspace carve(const tf_params* p)
     w.sim_v = off; off += sims;
     w.seg_tot = off; off += align256(tf::score_scratch_floats(d) * sizeof(float));
     w.keep_tmp = off; off += align256((size_t)p->batch * p->seq);
-    w.queue = off; off += align256(tf::kAttendQueueWords * sizeof(unsigned));
     w.total = off;
     return w;
 }
@@ -132,7 +131,7 @@ void mark(tf_ctx* ctx, int slot, int stage, hipStream_t s)
 
 tf_status run_attend(tf_ctx* ctx, const tf_params* p, const tf::Dims& d, const void* Q,
                      const void* K, const void* V, const int32_t* kept_idx,
-                     const uint8_t* keep, void* O, unsigned* queue, hipStream_t s, int slot)
+                     const uint8_t* keep, void* O, hipStream_t s, int slot)
 {
     const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
     if (p->dtype == TF_F32) {
@@ -142,10 +141,9 @@ tf_status run_attend(tf_ctx* ctx, const tf_params* p, const tf::Dims& d, const v
         return dev(ctx, tf::launch_attend_f32(d, scale, (const float*)Q, (const float*)K, (const float*)V,
                                               kept_idx, (float*)O, s), "fp32 attention launch");
     }
-    // the bf16 kernel writes the zero rows itself (the launch before this one has cleared its
-    // work-queue counters)
+    // the bf16 kernel writes the zero rows itself
     mark(ctx, slot, TF_STAGE_ATTEND, s);
-    return dev(ctx, tf::launch_attend_bf16(d, scale, Q, K, V, kept_idx, O, queue, ctx->n_cu, s),
+    return dev(ctx, tf::launch_attend_bf16(d, scale, Q, K, V, kept_idx, O, ctx->n_cu, s),
                "bf16 attention launch");
 }
 
@@ -260,7 +258,7 @@ tf_status tf_select(tf_ctx* ctx, const tf_params* p, const float* fused, uint8_t
     if (!fused || !keep || !kept_idx) return fail(ctx, TF_ERR_INVALID_ARG, "fused, keep and kept_idx must not be NULL");
     const tf::Dims d = make_dims(p, tf_keep_count(p->seq, p->prune_ratio));
     hipStream_t s = (hipStream_t)stream;
-    return dev(ctx, tf::launch_select_compact(d, p->warmup, fused, keep, kept_idx, tau, nullptr, s),
+    return dev(ctx, tf::launch_select_compact(d, p->warmup, fused, keep, kept_idx, tau, s),
                "select launch");
 }
 
@@ -278,13 +276,11 @@ tf_status tf_attend(tf_ctx* ctx, const tf_params* p, const void* Q, const void* 
     const tf::Dims d = make_dims(p, m);
     hipStream_t s = (hipStream_t)stream;
     uint8_t* keep = (uint8_t*)((char*)ws + w.keep_tmp);
-    unsigned* queue = (unsigned*)((char*)ws + w.queue);
-    if (p->dtype == TF_F32)  // the fp32 path zero-fills from a mask
-        st = dev(ctx, tf::launch_mask_from_idx(d, kept_idx, keep, nullptr, s), "mask launch");
-    else
-        st = dev(ctx, tf::launch_clear_queue(queue, s), "queue clear launch");
-    if (st != TF_OK) return st;
-    return run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, queue, s, -1);
+    if (p->dtype == TF_F32) {  // the fp32 path zero-fills from a mask
+        st = dev(ctx, tf::launch_mask_from_idx(d, kept_idx, keep, s), "mask launch");
+        if (st != TF_OK) return st;
+    }
+    return run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, s, -1);
 }
 
 tf_status tf_filtered_attention(tf_ctx* ctx, const tf_params* p, const void* Q, const void* K,
@@ -314,13 +310,12 @@ tf_status tf_filtered_attention(tf_ctx* ctx, const tf_params* p, const void* Q, 
     st = dev(ctx, tf::launch_fuse(d, p->fusion, sk, sv, fused, s), "fuse launch");
     if (st != TF_OK) return st;
     mark(ctx, slot, 2, s);
-    unsigned* queue = (unsigned*)(base + w.queue);
-    st = dev(ctx, tf::launch_select_compact(d, p->warmup, fused, keep, kept_idx, tau, queue, s),
+    st = dev(ctx, tf::launch_select_compact(d, p->warmup, fused, keep, kept_idx, tau, s),
              "select launch");
     if (st != TF_OK) return st;
     mark(ctx, slot, 3, s);  // compaction is part of the decision kernel
     mark(ctx, slot, 4, s);
-    st = run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, queue, s, slot);
+    st = run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, s, slot);
     if (st != TF_OK) return st;
     mark(ctx, slot, TF_N_STAGES, s);
     return TF_OK;
