@@ -39,6 +39,7 @@ def _load():
         i64, dbl, vp = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
         lib.tfo_num_threads.restype = ctypes.c_int
         lib.tfo_anchor_cosine.argtypes = [vp, i64, i64, i64, i64, vp, vp]
+        lib.tfo_anchor_cosine_ema.argtypes = [vp, i64, i64, i64, i64, dbl, vp, vp]
         lib.tfo_fuse.argtypes = [vp, vp, i64, i64, i64, ctypes.c_int, vp, vp]
         lib.tfo_keep_count.argtypes = [i64, dbl]
         lib.tfo_keep_count.restype = i64
@@ -74,6 +75,19 @@ def anchor_cosine(x, return_anchors: bool = False):
     anchors = np.empty((B, H, n, d), dtype=np.float64) if return_anchors else None
     _load().tfo_anchor_cosine(_p(xa), B, H, n, d, _p(cosv),
                               _p(anchors) if return_anchors else None)
+    return (cosv, anchors) if return_anchors else cosv
+
+
+def anchor_cosine_ema(x, gamma: float, return_anchors: bool = False):
+    """Per-head cosine of each token's row with the incremental anchor of Eq. 1 as it stands
+    before that token (anchor <- gamma * anchor + (1 - gamma) * row, from zero).
+    x: [B, H, n, d] -> cos [B, H, n] (float64); optionally the anchors [B, H, n, d]."""
+    xa = _f32(x)
+    B, H, n, d = xa.shape
+    cosv = np.empty((B, H, n), dtype=np.float64)
+    anchors = np.empty((B, H, n, d), dtype=np.float64) if return_anchors else None
+    _load().tfo_anchor_cosine_ema(_p(xa), B, H, n, d, float(gamma), _p(cosv),
+                                  _p(anchors) if return_anchors else None)
     return (cosv, anchors) if return_anchors else cosv
 
 
@@ -140,10 +154,15 @@ def attend_rows(q, k, v, kept_idx, rows, scale: float = 0.0):
 
 
 def filtered_attention(q, k, v, ratio: float, warmup: int = 1, mode: int = FUSE_EQ2,
-                       scale: float = 0.0, with_attention: bool = True):
-    """The whole path: score -> fuse -> select -> attend.  Returns a dict of numpy arrays."""
-    ck = anchor_cosine(k)
-    cv = anchor_cosine(v)
+                       scale: float = 0.0, with_attention: bool = True, ema_gamma=None):
+    """The whole path: score -> fuse -> select -> attend.  Returns a dict of numpy arrays.
+    ema_gamma: None for the exact-mean anchor, else the smoothing factor of Eq. 1."""
+    if ema_gamma is None:
+        ck = anchor_cosine(k)
+        cv = anchor_cosine(v)
+    else:
+        ck = anchor_cosine_ema(k, ema_gamma)
+        cv = anchor_cosine_ema(v, ema_gamma)
     S = fuse(ck, cv, mode)
     keep, idx, tau = select(S, ratio, warmup)
     out = {"sim_k": ck, "sim_v": cv, "fused": S, "keep": keep, "kept_idx": idx, "tau": tau}

@@ -57,6 +57,48 @@ int tfo_num_threads(void)
 #endif
 }
 
+/* Incremental anchor (Section 3.2, Eq. 1): Anchor <- gamma * Anchor + (1 - gamma) * x_current,
+ * one anchor per (b, h), starting from zero.  Row t is scored against the anchor as it stands
+ * BEFORE row t is folded in (the reading "previous keys" of the exact mean, kept here), so
+ * token 0 meets a zero anchor and scores 0 through the guard on the denominator.
+ * cosv: [B][H][n].  anchors (optional, may be NULL): [B][H][n][d], the anchor each row met. */
+void tfo_anchor_cosine_ema(const float *X, int64_t B, int64_t H, int64_t n, int64_t d,
+                           double gamma, double *cosv, double *anchors)
+{
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int64_t b = 0; b < B; ++b) {
+        for (int64_t h = 0; h < H; ++h) {
+            double *anchor = (double *)calloc((size_t)d, sizeof(double));
+            const float *xbh = X + ((b * H + h) * n) * d;
+            for (int64_t t = 0; t < n; ++t) {
+                const float *x = xbh + t * d;
+                if (anchors)
+                    memcpy(anchors + (((b * H + h) * n) + t) * d, anchor,
+                           (size_t)d * sizeof(double));
+                double dot = 0.0, na = 0.0, nx = 0.0;
+                for (int64_t c = 0; c < d; ++c) {
+                    double xc = (double)x[c];
+                    dot += anchor[c] * xc;
+                    na += anchor[c] * anchor[c];
+                    nx += xc * xc;
+                }
+                double den = sqrt(na) * sqrt(nx);
+                if (den < TFO_EPS_COS)
+                    den = TFO_EPS_COS;
+                double cs = dot / den;
+                if (cs > 1.0)
+                    cs = 1.0;
+                if (cs < -1.0)
+                    cs = -1.0;
+                cosv[(b * H + h) * n + t] = cs;
+                for (int64_t c = 0; c < d; ++c)
+                    anchor[c] = gamma * anchor[c] + (1.0 - gamma) * (double)x[c];
+            }
+            free(anchor);
+        }
+    }
+}
+
 /* Anchor (Algorithm 1, anchor lines; Section 3.2): for each (b, h, t) the mean of rows
  * 0..t-1 of X[b][h], and the cosine similarity of that mean with row t.
  * cosv: [B][H][n].  anchors (optional, may be NULL): [B][H][n][d], the means themselves. */

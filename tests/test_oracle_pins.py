@@ -100,6 +100,52 @@ def test_cosine_scale_invariance_and_mean_vs_sum():
     np.testing.assert_allclose(c1, ref, rtol=0, atol=1e-13)  # cos(mean, x) == cos(sum, x)
 
 
+
+# ------------------------------------------------------------------ incremental (EMA) anchor
+
+def test_ema_anchor_golden_worked_example(golden_dir):
+    tab = _load_table(os.path.join(golden_dir, "ema_anchor_worked_example.txt"))
+    x = tab[:, 1:3].astype(np.float32).reshape(1, 1, 4, 2)
+    cosv, anchors = oracle.anchor_cosine_ema(x, 0.5, return_anchors=True)
+    np.testing.assert_allclose(anchors[0, 0], tab[:, 3:5], rtol=0, atol=1e-15)
+    np.testing.assert_allclose(cosv[0, 0], tab[:, 5], rtol=0, atol=1e-15)
+
+
+def test_ema_anchor_brute_force_weights_and_special_cases():
+    rng = np.random.default_rng(11)
+    x = rng.normal(size=(2, 3, 40, 8)).astype(np.float32)
+    for gamma in (0.9, 0.5, 0.99):
+        cosv, anchors = oracle.anchor_cosine_ema(x, gamma, return_anchors=True)
+        # closed form of the recurrence: A_t = (1 - gamma) * sum_{j<t} gamma^(t-1-j) x_j
+        xd = x.astype(np.float64)
+        for t in (0, 1, 2, 7, 39):
+            w = (1 - gamma) * gamma ** (t - 1 - np.arange(t))
+            ref = np.einsum("j,bhjd->bhd", w, xd[:, :, :t]) if t else np.zeros((2, 3, 8))
+            np.testing.assert_allclose(anchors[:, :, t], ref, rtol=1e-12, atol=1e-15)
+            if t:
+                num = np.einsum("bhd,bhd->bh", ref, xd[:, :, t])
+                den = np.linalg.norm(ref, axis=-1) * np.linalg.norm(xd[:, :, t], axis=-1)
+                np.testing.assert_allclose(cosv[:, :, t], num / den, rtol=1e-12, atol=1e-15)
+        assert np.all(cosv[:, :, 0] == 0)                      # empty anchor
+        assert np.all(np.abs(cosv) <= 1)
+    # identical tokens: anchor = (1 - gamma^t) x, cosine 1 after the first
+    row = rng.normal(size=8).astype(np.float32)
+    same = np.broadcast_to(row, (1, 1, 30, 8)).copy()
+    c = oracle.anchor_cosine_ema(same, 0.9)
+    assert c[0, 0, 0] == 0 and np.all(np.abs(c[0, 0, 1:] - 1) <= 1e-12)
+    # gamma = 0: the anchor is the previous row alone
+    c0 = oracle.anchor_cosine_ema(x, 0.0)
+    xd = x.astype(np.float64)
+    prev, cur = xd[:, :, :-1], xd[:, :, 1:]
+    ref = np.einsum("bhtd,bhtd->bht", prev, cur) / (np.linalg.norm(prev, axis=-1) * np.linalg.norm(cur, axis=-1))
+    np.testing.assert_allclose(c0[:, :, 1:], ref, rtol=1e-12, atol=1e-15)
+    # the cosine does not see a power-of-two rescaling of the input
+    np.testing.assert_allclose(oracle.anchor_cosine_ema(x * 4, 0.9), oracle.anchor_cosine_ema(x, 0.9),
+                               rtol=1e-13, atol=1e-15)
+    # and differs from the exact-mean anchor (a different weighting, not a renaming)
+    assert np.abs(oracle.anchor_cosine_ema(x, 0.9) - oracle.anchor_cosine(x)).max() > 1e-3
+
+
 # ------------------------------------------------------------------ head statistics / fusion
 
 def test_fusion_golden_worked_example(golden_dir):
