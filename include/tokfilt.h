@@ -61,6 +61,13 @@ typedef enum {
     TF_FUSE_VALUE_ONLY = 3
 } tf_fusion;
 
+/* The anchor a token's key / value is compared with.
+ * TF_ANCHOR_MEAN  the exact mean of all previous rows (Algorithm 1, Section 3.2).
+ * TF_ANCHOR_EMA   the incremental anchor of Eq. 1: Anchor <- gamma * Anchor +
+ *                 (1 - gamma) * row, starting from zero; a row is compared with the anchor as
+ *                 it stands before that row is folded in. */
+typedef enum { TF_ANCHOR_MEAN = 0, TF_ANCHOR_EMA = 1 } tf_anchor;
+
 typedef struct {
     int32_t batch;
     int32_t n_q_heads;
@@ -77,6 +84,9 @@ typedef struct {
                               anchor */
     int32_t fusion;        /* tf_fusion */
     float softmax_scale;   /* 0 means 1 / sqrt(head_dim) */
+    int32_t anchor;        /* tf_anchor; 0 (the exact mean) is the default */
+    float ema_gamma;       /* smoothing factor of TF_ANCHOR_EMA, 0 <= gamma < 1 (the paper
+                              uses 0.9); ignored for TF_ANCHOR_MEAN */
     int32_t reserved;      /* must be 0 */
 } tf_params;
 
@@ -101,9 +111,11 @@ int32_t tf_keep_count(int32_t seq, double prune_ratio);
 size_t tf_workspace_bytes(const tf_params *p);
 
 /* Scoring (Algorithm 1 anchor / cosine / mean / var / alpha / s_KV lines; Eq. 2).
- * For each batch row b and position t: per KV head, the cosine of K[b,h,t] with the mean of
- * K[b,h,0..t-1] (0 for t = 0; denominator max(|a||x|, 1e-8); clamped to [-1, 1]), the same
- * for V, then the fusion selected by p->fusion.
+ * For each batch row b and position t: per KV head, the cosine of K[b,h,t] with the anchor
+ * selected by p->anchor: the mean of K[b,h,0..t-1], or the incremental anchor of Eq. 1 (0 for
+ * t = 0; denominator max(|a||x|, 1e-8); clamped to [-1, 1]), the same for V, then the fusion
+ * selected by p->fusion.  With TF_FUSE_KEY_ONLY (TF_FUSE_VALUE_ONLY) only K (V) is read, and
+ * sim_v (sim_k) is neither computed nor written.
  *   fused  out [batch][seq] float                      required
  *   sim_k  out [batch][n_kv_heads][seq] float          optional (NULL: kept in ws only)
  *   sim_v  out, same shape                             optional */

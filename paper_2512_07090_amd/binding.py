@@ -19,6 +19,7 @@ LIB_PATH = os.environ.get("TOKFILT_LIB") or os.path.join(_HERE, "libtokfilt.so")
 TF_OK, TF_ERR_INVALID_ARG, TF_ERR_UNSUPPORTED, TF_ERR_WORKSPACE_TOO_SMALL, TF_ERR_DEVICE = range(5)
 TF_F32, TF_BF16 = 0, 1
 TF_FUSE_EQ2, TF_FUSE_INVVAR, TF_FUSE_KEY_ONLY, TF_FUSE_VALUE_ONLY = range(4)
+TF_ANCHOR_MEAN, TF_ANCHOR_EMA = 0, 1
 TF_N_STAGES = 6
 STAGE_NAMES = ("score", "fuse", "select", "compact", "zero_rows", "attend")
 
@@ -35,7 +36,8 @@ class tf_params(ctypes.Structure):
                 ("q_stride", ctypes.c_int64 * 3), ("kv_stride", ctypes.c_int64 * 3),
                 ("o_stride", ctypes.c_int64 * 3), ("prune_ratio", ctypes.c_double),
                 ("warmup", ctypes.c_int32), ("fusion", ctypes.c_int32),
-                ("softmax_scale", ctypes.c_float), ("reserved", ctypes.c_int32)]
+                ("softmax_scale", ctypes.c_float), ("anchor", ctypes.c_int32),
+                ("ema_gamma", ctypes.c_float), ("reserved", ctypes.c_int32)]
 
 
 class TokfiltError(RuntimeError):
@@ -97,9 +99,10 @@ def _stream(stream):
 
 def make_params(q_shape, kv_shape, dtype: torch.dtype, prune_ratio: float, warmup: int = 1,
                 fusion: int = TF_FUSE_EQ2, softmax_scale: float = 0.0, q_stride=None,
-                kv_stride=None, o_stride=None) -> tf_params:
+                kv_stride=None, o_stride=None, ema_gamma=None) -> tf_params:
     """tf_params for contiguous [B, H, n, d] tensors unless strides (in elements, for batch,
-    head, position) are given."""
+    head, position) are given.  ema_gamma: None for the exact-mean anchor, else the smoothing
+    factor of the incremental anchor."""
     B, Hq, n, d = q_shape
     Hkv = kv_shape[1]
     p = tf_params()
@@ -112,6 +115,8 @@ def make_params(q_shape, kv_shape, dtype: torch.dtype, prune_ratio: float, warmu
         p.q_stride[i], p.kv_stride[i], p.o_stride[i] = qs[i], ks[i], os_[i]
     p.prune_ratio, p.warmup, p.fusion = float(prune_ratio), int(warmup), int(fusion)
     p.softmax_scale, p.reserved = float(softmax_scale), 0
+    p.anchor = TF_ANCHOR_MEAN if ema_gamma is None else TF_ANCHOR_EMA
+    p.ema_gamma = 0.0 if ema_gamma is None else float(ema_gamma)
     return p
 
 

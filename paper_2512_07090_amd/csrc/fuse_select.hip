@@ -28,8 +28,9 @@ __global__ __launch_bounds__(kFuseThreads) void fuse_kernel(const float* __restr
     const int hg = threadIdx.x / kFuseTokens;
     const int t = blockIdx.x * kFuseTokens + tok;
     if (t < n) {
-        const float* pk = sim_k + (long long)b * H * n + t;
-        const float* pv = sim_v + (long long)b * H * n + t;
+        // key-only / value-only scores read one tensor's cosines (the other was not computed)
+        const float* pk = (mode == 3 ? sim_v : sim_k) + (long long)b * H * n + t;
+        const float* pv = (mode == 2 ? sim_k : sim_v) + (long long)b * H * n + t;
         for (int h = hg; h < H; h += kFuseThreads / kFuseTokens) {
             ck[h * kFuseTokens + tok] = pk[(long long)h * n];
             cv[h * kFuseTokens + tok] = pv[(long long)h * n];

@@ -16,6 +16,8 @@
 // With nseg > 1 a first kernel reduces every segment but the last to its column totals and
 // the scan kernel starts from the sum of the totals before it.
 #include "tf_kernels.h"
+#include <algorithm>
+#include <cmath>
 
 namespace tf {
 
@@ -96,12 +98,12 @@ __device__ __forceinline__ void load_tile(Row8<T>* rows, const T* X, long long s
 template <typename T>
 __global__ __launch_bounds__(kThreads) void segment_totals_kernel(
     const T* __restrict__ K, const T* __restrict__ V, long long s_b, long long s_h, long long s_t,
-    int BH, int Hkv, int n, int nseg, int seg_len, float* __restrict__ seg_tot)
+    int BH, int Hkv, int n, int nseg, int seg_len, float* __restrict__ seg_tot, int first_tensor)
 {
     __shared__ float part[16][kHeadDim];
     const int seg = blockIdx.x % (nseg - 1);
     const int chain = blockIdx.x / (nseg - 1);
-    const int tensor = chain / BH, bh = chain % BH;
+    const int tensor = chain / BH + first_tensor, bh = chain % BH;
     const T* X = (tensor ? V : K) + (long long)(bh / Hkv) * s_b + (long long)(bh % Hkv) * s_h;
     const int l = threadIdx.x & 15, rg = threadIdx.x >> 4;
     const int t_begin = seg * seg_len;
@@ -129,17 +131,26 @@ __global__ __launch_bounds__(kThreads) void segment_totals_kernel(
     }
 }
 
-template <typename T>
+// EMA = false: the anchor is the exact mean of the rows before (Algorithm 1); EMA = true: the
+// incremental anchor of Eq. 1, A <- gamma A + (1 - gamma) x from zero, each row scored against
+// the anchor before it is folded in.  The same three phases carry a decay: a row group's total
+// is weighted towards its end, prefixes are multiplied by gamma^8 per row group and gamma^32 per
+// wave on their way, and a segment that does not start a chain is preceded by `warm` rows that
+// are only folded into the anchor (gamma^warm is below 1e-10, so what lies further back has
+// no weight left); no totals pass is needed.
+// first_tensor: 0 to walk K and V, or, with a single tensor (key-only / value-only scores),
+// the tensor to walk (0 = K, 1 = V).
+template <typename T, bool EMA>
 __global__ __launch_bounds__(kThreads) void scan_score_kernel(
     const T* __restrict__ K, const T* __restrict__ V, long long s_b, long long s_h, long long s_t,
     int BH, int Hkv, int n, int nseg, int seg_len, const float* __restrict__ seg_tot,
-    float* __restrict__ sim_k, float* __restrict__ sim_v)
+    float* __restrict__ sim_k, float* __restrict__ sim_v, int first_tensor, float gamma, int warm)
 {
     __shared__ float wtot[2][4][kHeadDim];
 
     const int seg = blockIdx.x % nseg;
     const int chain = blockIdx.x / nseg;
-    const int tensor = chain / BH, bh = chain % BH;
+    const int tensor = chain / BH + first_tensor, bh = chain % BH;
     const T* X = (tensor ? V : K) + (long long)(bh / Hkv) * s_b + (long long)(bh % Hkv) * s_h;
     float* sim = (tensor ? sim_v : sim_k) + (long long)bh * n;
 
@@ -149,13 +160,18 @@ __global__ __launch_bounds__(kThreads) void scan_score_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int rgw = (tid >> 4) & 3;  // row group inside the wave
 
-    const int t_begin = seg * seg_len;
-    const int t_end = min(n, t_begin + seg_len);
+    const int t_out = seg * seg_len;  // first row this workgroup writes a score for
+    const int t_begin = EMA ? max(0, t_out - warm) : t_out;
+    const int t_end = min(n, t_out + seg_len);
+    // decay factors of the incremental anchor
+    const float g1 = gamma, w1 = 1.0f - gamma;
+    const float g2 = g1 * g1, g4 = g2 * g2, g8 = g4 * g4, g16 = g8 * g8, g32 = g16 * g16;
+    const float g_rgw = rgw == 0 ? 1.0f : (rgw == 1 ? g8 : (rgw == 2 ? g16 : g16 * g8));
 
     float carry[8];
 #pragma unroll
     for (int c = 0; c < 8; ++c) carry[c] = 0.f;
-    for (int s = 0; s < seg; ++s) {
+    for (int s = 0; !EMA && s < seg; ++s) {
         const float* p = seg_tot + ((long long)chain * nseg + s) * kHeadDim + 8 * l;
         const float4 a = *reinterpret_cast<const float4*>(p);
         const float4 b = *reinterpret_cast<const float4*>(p + 4);
@@ -176,29 +192,33 @@ __global__ __launch_bounds__(kThreads) void scan_score_kernel(
         for (int c = 0; c < 8; ++c) {
             float s = x[0][c];
 #pragma unroll
-            for (int r = 1; r < kR; ++r) s += x[r][c];
-            tot[c] = s;
+            for (int r = 1; r < kR; ++r) s = EMA ? fmaf(g1, s, x[r][c]) : s + x[r][c];
+            tot[c] = EMA ? w1 * s : s;  // EMA: what these 8 rows add to the anchor after them
         }
-        // exclusive scan of the row-group totals inside the wave (4 row groups of 16 lanes)
+        // exclusive scan of the row-group totals inside the wave (4 row groups of 16 lanes);
+        // EMA: as seen at the start of this thread's row group
         float excl[8];
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
             float a = __shfl_up(tot[c], 16);
             a = rgw >= 1 ? a : 0.f;
-            const float pair = tot[c] + a;
+            const float pair = EMA ? fmaf(g8, a, tot[c]) : tot[c] + a;
             float b = __shfl_up(pair, 32);
             b = rgw >= 2 ? b : 0.f;
-            excl[c] = a + b;
+            excl[c] = EMA ? fmaf(g8, b, a) : a + b;
         }
         if (rgw == 3) {
             float4* dst = reinterpret_cast<float4*>(&wtot[parity][wave][8 * l]);
-            dst[0] = make_float4(excl[0] + tot[0], excl[1] + tot[1], excl[2] + tot[2], excl[3] + tot[3]);
-            dst[1] = make_float4(excl[4] + tot[4], excl[5] + tot[5], excl[6] + tot[6], excl[7] + tot[7]);
+            float wt[8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) wt[c] = EMA ? fmaf(g8, excl[c], tot[c]) : excl[c] + tot[c];
+            dst[0] = make_float4(wt[0], wt[1], wt[2], wt[3]);
+            dst[1] = make_float4(wt[4], wt[5], wt[6], wt[7]);
         }
         __syncthreads();
         float A[8], all[8];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) { A[c] = carry[c]; all[c] = 0.f; }
+        for (int c = 0; c < 8; ++c) { A[c] = carry[c]; all[c] = EMA ? carry[c] : 0.f; }
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             const float4* src = reinterpret_cast<const float4*>(&wtot[parity][w][8 * l]);
@@ -206,22 +226,32 @@ __global__ __launch_bounds__(kThreads) void scan_score_kernel(
             const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
 #pragma unroll
             for (int c = 0; c < 8; ++c) {
-                all[c] += v[c];
-                if (w < wave) A[c] += v[c];
+                if (EMA) {
+                    all[c] = fmaf(g32, all[c], v[c]);
+                    if (w < wave) A[c] = fmaf(g32, A[c], v[c]);
+                } else {
+                    all[c] += v[c];
+                    if (w < wave) A[c] += v[c];
+                }
             }
         }
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
-            carry[c] += all[c];
-            A[c] += excl[c];
+            if (EMA) {
+                carry[c] = all[c];
+                A[c] = fmaf(g_rgw, A[c], excl[c]);
+            } else {
+                carry[c] += all[c];
+                A[c] += excl[c];
+            }
         }
         parity ^= 1;
 
         // replay the 8 rows against the running prefix; lane r of the DPP row keeps row r.
         // |A|^2 is taken directly for the thread's first row and then advanced with
-        // |A + x|^2 = |A|^2 + 2 <A, x> + |x|^2 from the two reductions that are needed anyway.
-        // The chain's first tile takes it directly for every row: there the prefix is a sum of
-        // few rows and may cancel.
+        // |A + x|^2 = |A|^2 + 2 <A, x> + |x|^2 (EMA: |g A + w x|^2 = g^2 |A|^2 + 2 g w <A, x>
+        // + w^2 |x|^2) from the two reductions that are needed anyway.  The chain's first tile
+        // takes it directly for every row: there the prefix is a sum of few rows and may cancel.
         float my_dot = 0.f, my_aa = 0.f, my_xx = 0.f;
         float aa_run = 0.f;
 #pragma unroll
@@ -236,18 +266,20 @@ __global__ __launch_bounds__(kThreads) void scan_score_kernel(
                 aa_run = row16_sum(aa);
             }
 #pragma unroll
-            for (int c = 0; c < 8; ++c) A[c] += x[r][c];
+            for (int c = 0; c < 8; ++c) A[c] = EMA ? fmaf(g1, A[c], w1 * x[r][c]) : A[c] + x[r][c];
             dot = row16_sum(dot);
             const float xx = row16_sum(rows[r].sumsq());
             if (l == r) { my_dot = dot; my_aa = aa_run; my_xx = xx; }
-            aa_run = fmaf(2.f, dot, aa_run + xx);
+            aa_run = EMA ? fmaf(g2, aa_run, fmaf(2.f * g1 * w1, dot, w1 * w1 * xx))
+                         : fmaf(2.f, dot, aa_run + xx);
         }
         if (l < kR) {
             const int t = t0 + rg * kR + l;
-            if (t < t_end) {
+            if (t < t_end && t >= t_out) {
                 // cosine of row t with the MEAN of rows 0..t-1: numerator and denominator
                 // both carry the 1/t so that the 1e-8 floor applies to |mean| * |x|
-                const float inv_t = t > 0 ? 1.0f / (float)t : 0.f;
+                // (the incremental anchor is carried as it is and needs no factor)
+                const float inv_t = EMA ? 1.0f : (t > 0 ? 1.0f / (float)t : 0.f);
                 const float den = fmaxf(sqrtf(my_aa) * sqrtf(my_xx) * inv_t, 1e-8f);
                 float cs = (my_dot * inv_t) / den;
                 cs = fminf(1.f, fmaxf(-1.f, cs));
@@ -286,30 +318,61 @@ size_t score_scratch_floats(const Dims& d)
     return (size_t)2 * d.B * d.Hkv * p.nseg * kHeadDim;
 }
 
+// Rows of warm-up before a segment of the incremental anchor: gamma^rows <= 1e-10, in whole
+// tiles of the largest workgroup; 0 if no such count fits an int (gamma too close to one).
+static int ema_warm_rows(float gamma)
+{
+    if (!(gamma > 0.f)) return kTile;
+    const double rows = ceil(log(1e-10) / log((double)gamma));
+    if (!(rows < 1e8)) return 0;
+    return (int)((((long long)rows + kTile - 1) / kTile) * kTile);
+}
+
 template <typename T>
 static hipError_t launch_score_t(const Dims& d, const T* K, const T* V, float* sim_k,
-                                 float* sim_v, float* seg_tot, hipStream_t s)
+                                 float* sim_v, float* seg_tot, int tensors, int anchor,
+                                 float gamma, hipStream_t s)
 {
-    const ScorePlan p = plan_score(d.B, d.Hkv, d.n);
+    ScorePlan p = plan_score(d.B, d.Hkv, d.n);
     const int BH = d.B * d.Hkv;
-    const int chains = 2 * BH;
+    const int n_tensors = tensors == 0 ? 2 : 1;
+    const int first_tensor = tensors == 2 ? 1 : 0;
+    const int chains = n_tensors * BH;
+    if (anchor == 1) {
+        // segments only if their warm-up is at most as long as they are
+        const int warm = ema_warm_rows(gamma);
+        if (p.nseg > 1 && (warm == 0 || warm > p.seg_len)) {
+            const int want = warm == 0 ? 1 : std::max(1, d.n / warm);
+            const int tiles = (d.n + kTile - 1) / kTile;
+            const int nseg = std::max(1, std::min(want, p.nseg));
+            const int tiles_per_seg = (tiles + nseg - 1) / nseg;
+            p = ScorePlan{(tiles + tiles_per_seg - 1) / tiles_per_seg, tiles_per_seg * kTile};
+        }
+        scan_score_kernel<T, true><<<dim3(chains * p.nseg), dim3(kThreads), 0, s>>>(
+            K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k,
+            sim_v, first_tensor, gamma, warm);
+        return hipGetLastError();
+    }
     if (p.nseg > 1) {
         segment_totals_kernel<T><<<dim3(chains * (p.nseg - 1)), dim3(kThreads), 0, s>>>(
-            K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot);
+            K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot,
+            first_tensor);
     }
-    scan_score_kernel<T><<<dim3(chains * p.nseg), dim3(kThreads), 0, s>>>(
+    scan_score_kernel<T, false><<<dim3(chains * p.nseg), dim3(kThreads), 0, s>>>(
         K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k,
-        sim_v);
+        sim_v, first_tensor, 0.f, 0);
     return hipGetLastError();
 }
 
 hipError_t launch_score(const Dims& d, int dtype, const void* K, const void* V, float* sim_k,
-                        float* sim_v, float* seg_tot, hipStream_t s)
+                        float* sim_v, float* seg_tot, int tensors, int anchor, float gamma,
+                        hipStream_t s)
 {
     if (dtype == 0)
-        return launch_score_t<float>(d, (const float*)K, (const float*)V, sim_k, sim_v, seg_tot, s);
+        return launch_score_t<float>(d, (const float*)K, (const float*)V, sim_k, sim_v, seg_tot,
+                                     tensors, anchor, gamma, s);
     return launch_score_t<uint16_t>(d, (const uint16_t*)K, (const uint16_t*)V, sim_k, sim_v,
-                                    seg_tot, s);
+                                    seg_tot, tensors, anchor, gamma, s);
 }
 
 }  // namespace tf

@@ -26,8 +26,11 @@ struct ScorePlan {
 ScorePlan plan_score(int B, int Hkv, int n);
 size_t score_scratch_floats(const Dims& d);  // segment totals
 // sim_k / sim_v: [B][Hkv][n] float.  seg_tot: scratch of score_scratch_floats() floats.
+// tensors: 0 = K and V, 1 = K only, 2 = V only.  anchor: 0 = exact mean, 1 = incremental
+// anchor with smoothing factor gamma.
 hipError_t launch_score(const Dims& d, int dtype, const void* K, const void* V, float* sim_k,
-                        float* sim_v, float* seg_tot, hipStream_t s);
+                        float* sim_v, float* seg_tot, int tensors, int anchor, float gamma,
+                        hipStream_t s);
 
 // ---- head statistics + variance-aware fusion ----------------------------------------------
 hipError_t launch_fuse(const Dims& d, int fusion, const float* sim_k, const float* sim_v,

@@ -63,6 +63,10 @@ tf_status check_shape(const tf_params* p, const char** why)
     }
     if (p->warmup < 0) { *why = "warmup must be >= 0"; return TF_ERR_INVALID_ARG; }
     if (p->reserved != 0) { *why = "reserved must be 0"; return TF_ERR_INVALID_ARG; }
+    if (p->anchor != TF_ANCHOR_MEAN && p->anchor != TF_ANCHOR_EMA) { *why = "unknown anchor"; return TF_ERR_INVALID_ARG; }
+    if (p->anchor == TF_ANCHOR_EMA && !(p->ema_gamma >= 0.f && p->ema_gamma < 1.f)) {
+        *why = "ema_gamma must be in [0, 1)"; return TF_ERR_INVALID_ARG;
+    }
     if (!(p->softmax_scale >= 0.f) || isinf(p->softmax_scale)) {
         *why = "softmax_scale must be finite and >= 0"; return TF_ERR_INVALID_ARG;
     }
@@ -77,6 +81,12 @@ tf_status check_shape(const tf_params* p, const char** why)
     if (p->n_kv_heads > kMaxKvHeads) { *why = "more than 128 KV heads is not supported"; return TF_ERR_UNSUPPORTED; }
     if ((int64_t)p->batch * p->seq > (int64_t)1 << 30) { *why = "batch * seq too large"; return TF_ERR_UNSUPPORTED; }
     return TF_OK;
+}
+
+// which tensors the scoring kernel has to walk: 0 = both, 1 = K only, 2 = V only
+int score_tensors(const tf_params* p)
+{
+    return p->fusion == TF_FUSE_KEY_ONLY ? 1 : (p->fusion == TF_FUSE_VALUE_ONLY ? 2 : 0);
 }
 
 tf::Dims make_dims(const tf_params* p, int m)
@@ -244,7 +254,7 @@ tf_status tf_score(tf_ctx* ctx, const tf_params* p, const void* K, const void* V
     char* base = (char*)ws;
     float* sk = sim_k ? sim_k : (float*)(base + w.sim_k);
     float* sv = sim_v ? sim_v : (float*)(base + w.sim_v);
-    st = dev(ctx, tf::launch_score(d, p->dtype, K, V, sk, sv, (float*)(base + w.seg_tot), s), "score launch");
+    st = dev(ctx, tf::launch_score(d, p->dtype, K, V, sk, sv, (float*)(base + w.seg_tot), score_tensors(p), p->anchor, p->ema_gamma, s), "score launch");
     if (st != TF_OK) return st;
     return dev(ctx, tf::launch_fuse(d, p->fusion, sk, sv, fused, s), "fuse launch");
 }
@@ -304,7 +314,7 @@ tf_status tf_filtered_attention(tf_ctx* ctx, const tf_params* p, const void* Q, 
     if (ctx->timing_on && ctx->timing_calls < kMaxTimedCalls) slot = ctx->timing_calls++;
 
     mark(ctx, slot, 0, s);
-    st = dev(ctx, tf::launch_score(d, p->dtype, K, V, sk, sv, (float*)(base + w.seg_tot), s), "score launch");
+    st = dev(ctx, tf::launch_score(d, p->dtype, K, V, sk, sv, (float*)(base + w.seg_tot), score_tensors(p), p->anchor, p->ema_gamma, s), "score launch");
     if (st != TF_OK) return st;
     mark(ctx, slot, 1, s);
     st = dev(ctx, tf::launch_fuse(d, p->fusion, sk, sv, fused, s), "fuse launch");

@@ -30,9 +30,10 @@ def test_library_exports_every_declared_symbol():
 
 def test_params_struct_matches_header_layout():
     # 6 int32, 9 int64, double, 2 int32, float, int32 with natural alignment
-    assert ctypes.sizeof(B.tf_params) == 120
+    assert ctypes.sizeof(B.tf_params) == 128
     assert B.tf_params.q_stride.offset == 24 and B.tf_params.prune_ratio.offset == 96
-    assert B.tf_params.softmax_scale.offset == 112
+    assert B.tf_params.softmax_scale.offset == 112 and B.tf_params.anchor.offset == 116
+    assert B.tf_params.ema_gamma.offset == 120 and B.tf_params.reserved.offset == 124
 
 
 def test_keep_count_host(golden_dir):
@@ -68,6 +69,10 @@ def test_workspace_bytes_and_shape_validation():
     assert bad(fusion=4) == 0
     assert bad(warmup=-1) == 0
     assert bad(reserved=1) == 0
+    assert bad(anchor=2) == 0
+    assert bad(anchor=B.TF_ANCHOR_EMA, ema_gamma=1.0) == 0
+    assert bad(anchor=B.TF_ANCHOR_EMA, ema_gamma=-0.1) == 0
+    assert bad(anchor=B.TF_ANCHOR_EMA, ema_gamma=0.9) > 0
     p = B.make_params((2, 8, 300, 128), (2, 2, 300, 128), torch.bfloat16, 0.5)
     p.kv_stride[2] = 132                       # not a multiple of 8 elements
     assert B.tf_workspace_bytes(p) == 0

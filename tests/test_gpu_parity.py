@@ -109,14 +109,68 @@ def test_score_parity_small(ctx, shape):
     q, k, v, _ = synth.make_random_qkv(Bn, Hq, Hkv, n, 128, dtype=dt, seed=100 + n)
     p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.5)
     buf = B.Buffers(p, "cuda:0", with_sims=True)
+    ck, cv = oracle.anchor_cosine(k), oracle.anchor_cosine(v)
     for mode in (B.TF_FUSE_EQ2, B.TF_FUSE_INVVAR, B.TF_FUSE_KEY_ONLY, B.TF_FUSE_VALUE_ONLY):
+        p.fusion = mode
+        buf.sim_k.fill_(7.0)
+        buf.sim_v.fill_(7.0)
+        ctx.tf_score(p, k.cuda(), v.cuda(), buf.fused, buf.sim_k, buf.sim_v, buf.ws)
+        torch.cuda.synchronize()
+        # key-only / value-only scores walk one tensor; the other's cosines stay untouched
+        if mode != B.TF_FUSE_VALUE_ONLY:
+            assert_scores_close(buf.sim_k.cpu().numpy(), ck, "sim_k")
+        else:
+            assert torch.all(buf.sim_k == 7.0)
+        if mode != B.TF_FUSE_KEY_ONLY:
+            assert_scores_close(buf.sim_v.cpu().numpy(), cv, "sim_v")
+        else:
+            assert torch.all(buf.sim_v == 7.0)
+        assert_scores_close(buf.fused.cpu().numpy(), oracle.fuse(ck, cv, mode), "fused mode %d" % mode)
+
+
+@pytest.mark.parametrize("shape", [
+    # (dtype, B, Hq, Hkv, n, gamma): several tiles and a ragged tail; few chains (segments with a
+    # warm-up) and many; gamma close to one (warm-up longer than a segment), zero, the paper's
+    ("f32", 1, 4, 4, 1, 0.9), ("f32", 2, 4, 2, 300, 0.9), ("bf16", 2, 8, 2, 1000, 0.9),
+    ("bf16", 1, 32, 8, 4133, 0.9), ("bf16", 1, 8, 2, 6000, 0.99), ("f32", 1, 2, 1, 2049, 0.5),
+    ("bf16", 2, 8, 8, 700, 0.0), ("bf16", 1, 4, 1, 9000, 0.8), ("bf16", 4, 64, 64, 600, 0.95),
+])
+def test_score_parity_incremental_anchor(ctx, shape):
+    """The anchor of Eq. 1 (exponential moving average) instead of the exact mean."""
+    dt, Bn, Hq, Hkv, n, gamma = shape
+    _say("score ema %s" % (shape,))
+    q, k, v, _ = synth.make_random_qkv(Bn, Hq, Hkv, n, 128, dtype=dt, seed=300 + n)
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.5, ema_gamma=gamma)
+    buf = B.Buffers(p, "cuda:0", with_sims=True)
+    ck, cv = oracle.anchor_cosine_ema(k, gamma), oracle.anchor_cosine_ema(v, gamma)
+    for mode in (B.TF_FUSE_EQ2, B.TF_FUSE_KEY_ONLY, B.TF_FUSE_VALUE_ONLY):
         p.fusion = mode
         ctx.tf_score(p, k.cuda(), v.cuda(), buf.fused, buf.sim_k, buf.sim_v, buf.ws)
         torch.cuda.synchronize()
-        ck, cv = oracle.anchor_cosine(k), oracle.anchor_cosine(v)
-        assert_scores_close(buf.sim_k.cpu().numpy(), ck, "sim_k")
-        assert_scores_close(buf.sim_v.cpu().numpy(), cv, "sim_v")
+        if mode != B.TF_FUSE_VALUE_ONLY:
+            assert_scores_close(buf.sim_k.cpu().numpy(), ck, "sim_k")
+        if mode != B.TF_FUSE_KEY_ONLY:
+            assert_scores_close(buf.sim_v.cpu().numpy(), cv, "sim_v")
         assert_scores_close(buf.fused.cpu().numpy(), oracle.fuse(ck, cv, mode), "fused mode %d" % mode)
+
+
+def test_whole_path_incremental_anchor(ctx):
+    _say("whole path ema")
+    w = synth.scaled(synth.workload(1), batch=2, seq=1800, n_q_heads=8, n_kv_heads=8)
+    q, k, v, _ = synth.make_qkv(w)
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.5, ema_gamma=0.9)
+    buf = B.Buffers(p, "cuda:0")
+    buf.O.fill_(float("nan"))
+    ctx.tf_filtered_attention(p, q.cuda(), k.cuda(), v.cuda(), buf.keep, buf.kept_idx, buf.fused,
+                              buf.tau, buf.O, buf.ws)
+    torch.cuda.synchronize()
+    ref = oracle.filtered_attention(q, k, v, 0.5, with_attention=False, ema_gamma=0.9)
+    assert_scores_close(buf.fused.cpu().numpy(), ref["fused"], "fused")
+    keep_g, idx_g = buf.keep.cpu().numpy(), buf.kept_idx.cpu().numpy()
+    assert_mask_parity(keep_g, idx_g, ref["fused"], 0.5, 1, ref["keep"], ref["tau"])
+    O_ref = oracle.attend(q, k, v, idx_g)
+    O_g = buf.O.float().cpu().numpy().astype(np.float64)
+    assert np.abs(O_g - O_ref).max() <= ATTN_TOL[q.dtype]
 
 
 def test_score_degenerate_inputs(ctx):
