@@ -150,6 +150,27 @@ tf_status tf_filtered_attention(tf_ctx *ctx, const tf_params *p, const void *Q, 
                                 const void *V, uint8_t *keep, int32_t *kept_idx, float *fused,
                                 float *tau, void *O, void *ws, size_t ws_bytes, void *stream);
 
+/* Tail-focused layer schedule (Section 3.3, Eq. 3), host side: to meet the global budget
+ * p_global in [0, 1], the last ceil(tail_fraction * n_layers) layers (0 < tail_fraction <= 1)
+ * are pruned at p_global / tail_fraction (not above 1), the others at 0.
+ * ratios: host array [n_layers]; *n_tail (may be NULL): number of selected layers. */
+tf_status tf_tail_schedule(int32_t n_layers, double p_global, double tail_fraction,
+                           double *ratios, int32_t *n_tail);
+
+/* Tail-focused multi-layer driver (Section 3.3): the whole path on n_layers layers of one shape
+ * `p`, layer l at pruning ratio ratios[l] (p->prune_ratio is ignored; every ratio in [0, 1)).
+ * A layer at ratio 0 does no scoring: all its tokens are kept (keep = 1, kept_idx = 0..seq-1,
+ * tau = +inf, fused not written) and it runs plain causal attention.  Q, K, V, O, keep,
+ * kept_idx, fused, tau: host arrays of n_layers device pointers, each as in
+ * tf_filtered_attention (kept_idx[l] holds [batch][tf_keep_count(seq, ratios[l])]); tau may be
+ * NULL.  One workspace of tf_workspace_bytes(p) serves all layers in stream order. */
+tf_status tf_filtered_attention_layers(tf_ctx *ctx, const tf_params *p, int32_t n_layers,
+                                       const double *ratios, const void *const *Q,
+                                       const void *const *K, const void *const *V,
+                                       uint8_t *const *keep, int32_t *const *kept_idx,
+                                       float *const *fused, float *const *tau, void *const *O,
+                                       void *ws, size_t ws_bytes, void *stream);
+
 /* Per-stage device timing for measurement.  While enabled, every tf_filtered_attention call
  * brackets its stages with events on the caller's stream (at most 256 calls are recorded
  * between reads).  tf_stage_timing_read waits for those events, writes the summed

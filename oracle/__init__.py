@@ -42,6 +42,8 @@ def _load():
         lib.tfo_anchor_cosine_ema.argtypes = [vp, i64, i64, i64, i64, dbl, vp, vp]
         lib.tfo_fuse.argtypes = [vp, vp, i64, i64, i64, ctypes.c_int, vp, vp]
         lib.tfo_keep_count.argtypes = [i64, dbl]
+        lib.tfo_tail_schedule.argtypes = [i64, dbl, dbl, vp]
+        lib.tfo_tail_schedule.restype = i64
         lib.tfo_keep_count.restype = i64
         lib.tfo_select.argtypes = [vp, i64, i64, i64, i64, vp, vp, vp]
         lib.tfo_attend.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, vp, i64, dbl, vp]
@@ -102,6 +104,16 @@ def fuse(cos_k, cos_v, mode: int = FUSE_EQ2, return_stats: bool = False):
     _load().tfo_fuse(_p(ck), _p(cv), B, H, n, int(mode), _p(S),
                      _p(stats) if return_stats else None)
     return (S, stats) if return_stats else S
+
+
+def tail_schedule(n_layers: int, p_global: float, y: float):
+    """Per-layer pruning ratios of the tail-focused schedule (Eq. 3): the last fraction y of
+    the layers at p_global / y, the rest at 0.  Returns (ratios [n_layers], n_tail)."""
+    ratios = np.zeros(int(n_layers), dtype=np.float64)
+    n_tail = int(_load().tfo_tail_schedule(int(n_layers), float(p_global), float(y), _p(ratios)))
+    if n_tail < 0:
+        raise ValueError("tail_schedule: arguments out of range")
+    return ratios, n_tail
 
 
 def keep_count(n: int, ratio: float) -> int:

@@ -191,6 +191,26 @@ void tfo_fuse(const double *cK, const double *cV, int64_t B, int64_t H, int64_t 
     }
 }
 
+/* Tail-focused layer schedule (Section 3.3, Eq. 3): to meet a global budget p_global the last
+ * fraction y of the layers is pruned at p_tail = p_global / y (not above 1) and the other layers
+ * are not pruned at all.  Reading: "the last y fraction" of L layers is the last ceil(y * L - 1e-9)
+ * of them.  ratios: [n_layers], front layers 0.  Returns the number of selected layers, or -1
+ * for arguments outside n_layers >= 1, 0 <= p_global <= 1, 0 < y <= 1. */
+int64_t tfo_tail_schedule(int64_t n_layers, double p_global, double y, double *ratios)
+{
+    if (n_layers < 1 || !(p_global >= 0.0 && p_global <= 1.0) || !(y > 0.0 && y <= 1.0))
+        return -1;
+    int64_t n_tail = (int64_t)ceil(y * (double)n_layers - 1e-9);
+    if (n_tail < 1)
+        n_tail = 1;
+    double p_tail = p_global / y;
+    if (p_tail > 1.0)
+        p_tail = 1.0;
+    for (int64_t l = 0; l < n_layers; ++l)
+        ratios[l] = (l >= n_layers - n_tail) ? p_tail : 0.0;
+    return n_tail;
+}
+
 /* Number of kept tokens for pruning ratio r over n tokens. */
 int64_t tfo_keep_count(int64_t n, double r)
 {

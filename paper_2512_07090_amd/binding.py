@@ -26,7 +26,7 @@ STAGE_NAMES = ("score", "fuse", "select", "compact", "zero_rows", "attend")
 EXPORTS = ("tf_create", "tf_destroy", "tf_status_string", "tf_last_error", "tf_keep_count",
            "tf_workspace_bytes", "tf_score", "tf_select", "tf_attend", "tf_filtered_attention",
            "tf_stage_timing_enable", "tf_stage_timing_read", "tf_probe_hbm_read",
-           "tf_probe_mfma_bf16")
+           "tf_probe_mfma_bf16", "tf_tail_schedule", "tf_filtered_attention_layers")
 
 
 class tf_params(ctypes.Structure):
@@ -77,6 +77,12 @@ def lib():
         L.tf_filtered_attention.argtypes = [vp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.tf_stage_timing_enable.argtypes = [vp, ctypes.c_int]
         L.tf_stage_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+        dp = ctypes.POINTER(ctypes.c_double)
+        vpp = ctypes.POINTER(vp)
+        L.tf_tail_schedule.argtypes = [i32, ctypes.c_double, ctypes.c_double, dp, ctypes.POINTER(i32)]
+        L.tf_tail_schedule.restype = ctypes.c_int
+        L.tf_filtered_attention_layers.argtypes = [vp, pp, i32, dp] + [vpp] * 8 + [vp, sz, vp]
+        L.tf_filtered_attention_layers.restype = ctypes.c_int
         L.tf_probe_hbm_read.argtypes = [vp, vp, sz, vp, vp, ctypes.POINTER(ctypes.c_double)]
         L.tf_probe_mfma_bf16.argtypes = [vp, i32, vp, vp, ctypes.POINTER(ctypes.c_double)]
         for name in ("tf_score", "tf_select", "tf_attend", "tf_filtered_attention",
@@ -118,6 +124,17 @@ def make_params(q_shape, kv_shape, dtype: torch.dtype, prune_ratio: float, warmu
     p.anchor = TF_ANCHOR_MEAN if ema_gamma is None else TF_ANCHOR_EMA
     p.ema_gamma = 0.0 if ema_gamma is None else float(ema_gamma)
     return p
+
+
+def tf_tail_schedule(n_layers: int, p_global: float, tail_fraction: float):
+    """Per-layer pruning ratios of the tail-focused schedule; returns (ratios, n_tail)."""
+    ratios = (ctypes.c_double * max(int(n_layers), 1))()
+    n_tail = ctypes.c_int32()
+    st = lib().tf_tail_schedule(int(n_layers), float(p_global), float(tail_fraction), ratios,
+                                ctypes.byref(n_tail))
+    if st != TF_OK:
+        raise TokfiltError(st, "tf_tail_schedule: " + tf_status_string(st))
+    return [float(x) for x in ratios[:n_layers]], int(n_tail.value)
 
 
 def tf_status_string(status: int) -> str:
@@ -182,6 +199,21 @@ class Context:
         self._check(lib().tf_filtered_attention(
             self._h, ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(keep), _ptr(kept_idx),
             _ptr(fused), _ptr(tau), _ptr(O), _ptr(ws),
+            0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
+
+    def tf_filtered_attention_layers(self, p, ratios, Q, K, V, keep, kept_idx, fused, tau, O, ws,
+                                     stream=None):
+        """Q .. O: lists of per-layer tensors (tau may be None)."""
+        n_layers = len(ratios)
+
+        def arr(ts):
+            if ts is None:
+                return None
+            return (ctypes.c_void_p * n_layers)(*[None if t is None else t.data_ptr() for t in ts])
+        r = (ctypes.c_double * n_layers)(*[float(x) for x in ratios])
+        self._check(lib().tf_filtered_attention_layers(
+            self._h, ctypes.byref(p), n_layers, r, arr(Q), arr(K), arr(V), arr(keep),
+            arr(kept_idx), arr(fused), arr(tau), arr(O), _ptr(ws),
             0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
 
     def tf_stage_timing_enable(self, on: bool):

@@ -368,6 +368,25 @@ hipError_t launch_compact(const Dims& d, const uint8_t* keep, int32_t* kept_idx,
     return hipGetLastError();
 }
 
+__global__ void keep_all_kernel(int n, uint8_t* __restrict__ keep, int32_t* __restrict__ kept_idx,
+                                float* __restrict__ tau)
+{
+    const int b = blockIdx.y;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) {
+        keep[(long long)b * n + i] = 1;
+        kept_idx[(long long)b * n + i] = i;
+    }
+    if (tau && i == 0) tau[b] = INFINITY;
+}
+
+hipError_t launch_keep_all(const Dims& d, uint8_t* keep, int32_t* kept_idx, float* tau,
+                           hipStream_t s)
+{
+    keep_all_kernel<<<dim3((d.n + 255) / 256, d.B), dim3(256), 0, s>>>(d.n, keep, kept_idx, tau);
+    return hipGetLastError();
+}
+
 hipError_t launch_mask_from_idx(const Dims& d, const int32_t* kept_idx, uint8_t* keep,
                                 hipStream_t s)
 {

@@ -44,6 +44,9 @@ hipError_t launch_compact(const Dims& d, const uint8_t* keep, int32_t* kept_idx,
 // kernels above)
 hipError_t launch_select_compact(const Dims& d, int warmup, const float* fused, uint8_t* keep,
                                  int32_t* kept_idx, float* tau, hipStream_t s);
+// every token kept: keep = 1, kept_idx = 0 .. n-1, tau = +inf (tau may be null)
+hipError_t launch_keep_all(const Dims& d, uint8_t* keep, int32_t* kept_idx, float* tau,
+                           hipStream_t s);
 // keep mask from an index list (for callers that bring their own kept set)
 hipError_t launch_mask_from_idx(const Dims& d, const int32_t* kept_idx, uint8_t* keep,
                                 hipStream_t s);

@@ -161,6 +161,38 @@ tf_status run_attend(tf_ctx* ctx, const tf_params* p, const tf::Dims& d, const v
 
 namespace {
 
+// score -> fuse -> select + compact -> attend for one layer (arguments already validated)
+tf_status run_path(tf_ctx* ctx, const tf_params* p, const Workspace& w, const void* Q,
+                   const void* K, const void* V, uint8_t* keep, int32_t* kept_idx, float* fused,
+                   float* tau, void* O, void* ws, hipStream_t s)
+{
+    const tf::Dims d = make_dims(p, tf_keep_count(p->seq, p->prune_ratio));
+    char* base = (char*)ws;
+    float* sk = (float*)(base + w.sim_k);
+    float* sv = (float*)(base + w.sim_v);
+
+    int slot = -1;
+    if (ctx->timing_on && ctx->timing_calls < kMaxTimedCalls) slot = ctx->timing_calls++;
+
+    mark(ctx, slot, 0, s);
+    tf_status st = dev(ctx, tf::launch_score(d, p->dtype, K, V, sk, sv, (float*)(base + w.seg_tot),
+                                             score_tensors(p), p->anchor, p->ema_gamma, s), "score launch");
+    if (st != TF_OK) return st;
+    mark(ctx, slot, 1, s);
+    st = dev(ctx, tf::launch_fuse(d, p->fusion, sk, sv, fused, s), "fuse launch");
+    if (st != TF_OK) return st;
+    mark(ctx, slot, 2, s);
+    st = dev(ctx, tf::launch_select_compact(d, p->warmup, fused, keep, kept_idx, tau, s),
+             "select launch");
+    if (st != TF_OK) return st;
+    mark(ctx, slot, 3, s);  // compaction is part of the decision kernel
+    mark(ctx, slot, 4, s);
+    st = run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, s, slot);
+    if (st != TF_OK) return st;
+    mark(ctx, slot, TF_N_STAGES, s);
+    return TF_OK;
+}
+
 // one warm-up and one timed launch of `launch`, milliseconds of the timed one
 template <class F>
 tf_status time_probe(tf_ctx* ctx, hipStream_t s, F launch, float* ms)
@@ -304,30 +336,59 @@ tf_status tf_filtered_attention(tf_ctx* ctx, const tf_params* p, const void* Q, 
         return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V, O, keep, kept_idx and fused must not be NULL");
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O))
         return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V and O must be 16-byte aligned");
-    const tf::Dims d = make_dims(p, tf_keep_count(p->seq, p->prune_ratio));
+    return run_path(ctx, p, w, Q, K, V, keep, kept_idx, fused, tau, O, ws, (hipStream_t)stream);
+}
+
+tf_status tf_tail_schedule(int32_t n_layers, double p_global, double tail_fraction,
+                           double* ratios, int32_t* n_tail)
+{
+    if (n_layers < 1 || !ratios || !(p_global >= 0.0 && p_global <= 1.0) ||
+        !(tail_fraction > 0.0 && tail_fraction <= 1.0))
+        return TF_ERR_INVALID_ARG;
+    int32_t nt = (int32_t)ceil(tail_fraction * (double)n_layers - 1e-9);
+    if (nt < 1) nt = 1;
+    const double p_tail = fmin(p_global / tail_fraction, 1.0);
+    for (int32_t l = 0; l < n_layers; ++l) ratios[l] = l >= n_layers - nt ? p_tail : 0.0;
+    if (n_tail) *n_tail = nt;
+    return TF_OK;
+}
+
+tf_status tf_filtered_attention_layers(tf_ctx* ctx, const tf_params* p, int32_t n_layers,
+                                       const double* ratios, const void* const* Q,
+                                       const void* const* K, const void* const* V,
+                                       uint8_t* const* keep, int32_t* const* kept_idx,
+                                       float* const* fused, float* const* tau, void* const* O,
+                                       void* ws, size_t ws_bytes, void* stream)
+{
+    Workspace w;
+    tf_status st = enter(ctx, p, ws, ws_bytes, &w);
+    if (st != TF_OK) return st;
+    if (n_layers < 1 || !ratios || !Q || !K || !V || !O || !keep || !kept_idx || !fused)
+        return fail(ctx, TF_ERR_INVALID_ARG, "n_layers >= 1 and the ratio and pointer arrays are required");
+    // everything is checked before the first launch
+    for (int32_t l = 0; l < n_layers; ++l) {
+        if (!(ratios[l] >= 0.0 && ratios[l] < 1.0))
+            return fail(ctx, TF_ERR_INVALID_ARG, "ratio of layer %d must be in [0, 1)", l);
+        if (!Q[l] || !K[l] || !V[l] || !O[l] || !keep[l] || !kept_idx[l] || (ratios[l] > 0.0 && !fused[l]))
+            return fail(ctx, TF_ERR_INVALID_ARG, "a pointer of layer %d is NULL", l);
+        if (misaligned(Q[l]) || misaligned(K[l]) || misaligned(V[l]) || misaligned(O[l]))
+            return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V and O of layer %d must be 16-byte aligned", l);
+    }
     hipStream_t s = (hipStream_t)stream;
-    char* base = (char*)ws;
-    float* sk = (float*)(base + w.sim_k);
-    float* sv = (float*)(base + w.sim_v);
-
-    int slot = -1;
-    if (ctx->timing_on && ctx->timing_calls < kMaxTimedCalls) slot = ctx->timing_calls++;
-
-    mark(ctx, slot, 0, s);
-    st = dev(ctx, tf::launch_score(d, p->dtype, K, V, sk, sv, (float*)(base + w.seg_tot), score_tensors(p), p->anchor, p->ema_gamma, s), "score launch");
-    if (st != TF_OK) return st;
-    mark(ctx, slot, 1, s);
-    st = dev(ctx, tf::launch_fuse(d, p->fusion, sk, sv, fused, s), "fuse launch");
-    if (st != TF_OK) return st;
-    mark(ctx, slot, 2, s);
-    st = dev(ctx, tf::launch_select_compact(d, p->warmup, fused, keep, kept_idx, tau, s),
-             "select launch");
-    if (st != TF_OK) return st;
-    mark(ctx, slot, 3, s);  // compaction is part of the decision kernel
-    mark(ctx, slot, 4, s);
-    st = run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, s, slot);
-    if (st != TF_OK) return st;
-    mark(ctx, slot, TF_N_STAGES, s);
+    for (int32_t l = 0; l < n_layers; ++l) {
+        tf_params pl = *p;
+        pl.prune_ratio = ratios[l];
+        float* tau_l = tau ? tau[l] : nullptr;
+        if (tf_keep_count(p->seq, ratios[l]) == p->seq) {
+            // nothing to filter: no scoring, every token kept, plain causal attention
+            const tf::Dims d = make_dims(&pl, p->seq);
+            st = dev(ctx, tf::launch_keep_all(d, keep[l], kept_idx[l], tau_l, s), "keep-all launch");
+            if (st == TF_OK) st = run_attend(ctx, &pl, d, Q[l], K[l], V[l], kept_idx[l], keep[l], O[l], s, -1);
+        } else {
+            st = run_path(ctx, &pl, w, Q[l], K[l], V[l], keep[l], kept_idx[l], fused[l], tau_l, O[l], ws, s);
+        }
+        if (st != TF_OK) return st;
+    }
     return TF_OK;
 }
 

@@ -95,3 +95,15 @@ def test_product_path_has_no_oracle_dependency():
                 src = open(os.path.join(dirpath, f)).read()
                 assert "import oracle" not in src and "from oracle" not in src
                 assert "tokfilt_oracle" not in src
+
+
+def test_tail_schedule_host_matches_oracle():
+    import oracle
+    for L, pg, y in ((32, 0.25, 0.5), (40, 0.33, 0.4), (40, 0.33, 0.6), (10, 0.3, 0.25), (7, 0.9, 0.5),
+                     (1, 0.5, 1.0)):
+        ratios, n_tail = B.tf_tail_schedule(L, pg, y)
+        ref, n_ref = oracle.tail_schedule(L, pg, y)
+        assert n_tail == n_ref and ratios == list(ref)
+    for bad in ((0, 0.2, 0.5), (4, -0.1, 0.5), (4, 0.2, 0.0), (4, 0.2, 1.5)):
+        with pytest.raises(B.TokfiltError):
+            B.tf_tail_schedule(*bad)

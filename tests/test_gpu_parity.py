@@ -523,3 +523,50 @@ def test_whole_path_replays_from_a_captured_graph(ctx):
             assert torch.equal(got, ref), "replay %d differs from the eager result" % rep
         step()                                   # eager work between replays
         torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------ tail-focused layers
+
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_tail_focused_layers_match_the_oracle_layer_by_layer(ctx, dt):
+    """Four synthetic layers of one shape, a 25 % budget on the last half: layers 0 and 1 keep
+    every token and run dense causal attention, layers 2 and 3 run the path at 50 %."""
+    _say("tail-focused layers %s" % dt)
+    L, Bn, Hq, Hkv, n = 4, 2, 4, 2, 700
+    ratios, n_tail = B.tf_tail_schedule(L, 0.25, 0.5)
+    assert ratios == [0.0, 0.0, 0.5, 0.5] and n_tail == 2
+    layers = [synth.make_random_qkv(Bn, Hq, Hkv, n, 128, dtype=dt, seed=900 + l)[:3] for l in range(L)]
+    p = B.make_params((Bn, Hq, n, 128), (Bn, Hkv, n, 128), layers[0][0].dtype, 0.0)
+    bufs = []
+    for r in ratios:
+        p.prune_ratio = r
+        b_ = B.Buffers(p, "cuda:0")
+        b_.O.fill_(float("nan"))
+        b_.fused.fill_(-5.0)
+        bufs.append(b_)
+    dev = [[t.cuda() for t in lay] for lay in layers]
+    ctx.tf_filtered_attention_layers(
+        p, ratios, [d_[0] for d_ in dev], [d_[1] for d_ in dev], [d_[2] for d_ in dev],
+        [b_.keep for b_ in bufs], [b_.kept_idx for b_ in bufs], [b_.fused for b_ in bufs],
+        [b_.tau for b_ in bufs], [b_.O for b_ in bufs], bufs[0].ws)
+    torch.cuda.synchronize()
+    for l, (r, b_) in enumerate(zip(ratios, bufs)):
+        q, k, v = layers[l]
+        keep_g, idx_g = b_.keep.cpu().numpy(), b_.kept_idx.cpu().numpy()
+        if r == 0.0:
+            assert np.all(keep_g == 1) and np.all(idx_g == np.arange(n))
+            assert torch.all(torch.isinf(b_.tau)) and torch.all(b_.fused == -5.0)   # no scoring
+        else:
+            ref = oracle.filtered_attention(q, k, v, r, with_attention=False)
+            assert_scores_close(b_.fused.cpu().numpy(), ref["fused"], "fused layer %d" % l)
+            assert_mask_parity(keep_g, idx_g, ref["fused"], r, 1, ref["keep"], ref["tau"])
+        O_ref = oracle.attend(q, k, v, idx_g)
+        O_g = b_.O.float().cpu().numpy().astype(np.float64)
+        assert not np.isnan(O_g).any()
+        assert np.abs(O_g - O_ref).max() <= ATTN_TOL[q.dtype], "layer %d" % l
+    # argument errors are found before anything is enqueued
+    with pytest.raises(B.TokfiltError):
+        ctx.tf_filtered_attention_layers(
+            p, [0.0, 0.0, 0.5, 1.0], [d_[0] for d_ in dev], [d_[1] for d_ in dev],
+            [d_[2] for d_ in dev], [b_.keep for b_ in bufs], [b_.kept_idx for b_ in bufs],
+            [b_.fused for b_ in bufs], None, [b_.O for b_ in bufs], bufs[0].ws)

@@ -208,6 +208,40 @@ def test_gqa_scoring_equals_repeated_heads():
     np.testing.assert_allclose(S, Sr, rtol=0, atol=1e-13)
 
 
+
+# ------------------------------------------------------------------ tail-focused schedule
+
+def test_tail_schedule_paper_examples_and_budget():
+    # Section 3.3's own example: a 25 % global budget on the last half of the layers is 50 % there
+    r, n_tail = oracle.tail_schedule(32, 0.25, 0.5)
+    assert n_tail == 16 and np.all(r[:16] == 0) and np.all(r[16:] == 0.5)
+    # the hyper-parameter table of the appendix: 33 % on LLaMA-2-13B (40 layers), Y in 0.4 .. 0.6
+    for y, count, ratio in ((0.4, 16, 0.825), (0.5, 20, 0.66), (0.6, 24, 0.55)):
+        r, n_tail = oracle.tail_schedule(40, 0.33, y)
+        assert n_tail == count
+        np.testing.assert_allclose(r[40 - count:], ratio, rtol=1e-15)
+        assert np.all(r[:40 - count] == 0)
+        np.testing.assert_allclose(r.mean(), 0.33, rtol=1e-12)      # the budget is met exactly
+    # Eq. 3 in exact rationals whenever y * L is whole; the tail is never pruned above 1
+    for L in (1, 7, 32, 40, 80):
+        for num, den in ((1, 1), (1, 2), (1, 4), (3, 4)):
+            if (L * num) % den:
+                continue
+            for pg in (Fraction(0), Fraction(1, 10), Fraction(1, 4), Fraction(1, 2)):
+                r, n_tail = oracle.tail_schedule(L, float(pg), num / den)
+                assert n_tail == L * num // den
+                want = min(pg * den / num, Fraction(1))
+                np.testing.assert_allclose(r[L - n_tail:], float(want), rtol=1e-15, atol=0)
+                assert np.all(r[:L - n_tail] == 0)
+    r, n_tail = oracle.tail_schedule(10, 0.9, 0.5)
+    assert np.all(r[5:] == 1.0)
+    r, n_tail = oracle.tail_schedule(10, 0.3, 0.25)                   # 2.5 layers -> 3
+    assert n_tail == 3
+    for bad in ((0, 0.2, 0.5), (4, -0.1, 0.5), (4, 0.2, 0.0), (4, 0.2, 1.5)):
+        with pytest.raises(ValueError):
+            oracle.tail_schedule(*bad)
+
+
 # ------------------------------------------------------------------ count / selection
 
 def test_keep_count_golden(golden_dir):
