@@ -274,6 +274,46 @@ void tfo_select(const float *S32, int64_t B, int64_t n, int64_t m, int64_t W, ui
     }
 }
 
+/* Online decision with an adaptive threshold (Algorithm 1, threshold and skip lines; warm-up of
+ * Section 3.2; feedback rule of Section 3.3, Eq. 4).  Tokens of a row are visited in order.
+ * Before token t is judged the threshold moves by eta * (P_current - P_target), where P_current
+ * is the fraction of the t tokens seen so far that were skipped (0 for t = 0); the threshold is
+ * updated during the first W tokens too, but those are never skipped; after that token t is
+ * skipped iff S_t > tau.
+ * Readings.  (1) Sign: Eq. 4 (tau rises when too much has been skipped, negative feedback) is
+ * followed; Algorithm 1 prints eta * (target - current), which would push the ratio away from the
+ * target.  (2) Arithmetic, fixed so that an implementation can agree bit for bit: everything in
+ * float; P_current = (float)skipped * (1.0f / (float)t); tau = fmaf(eta, P_current - target, tau).
+ * S32: [B][n].  keep: [B][n] 0/1.  kept_idx: [B][n], the first count[b] entries of row b are the
+ * kept positions ascending, the rest is -1.  count: [B].  tau_out: [B], the threshold after the
+ * last token. */
+void tfo_select_online(const float *S32, int64_t B, int64_t n, int64_t W, float target, float eta,
+                       float tau0, uint8_t *keep, int32_t *kept_idx, int32_t *count,
+                       float *tau_out)
+{
+    for (int64_t b = 0; b < B; ++b) {
+        const float *s = S32 + b * n;
+        float tau = tau0;
+        int64_t skipped = 0, kept = 0;
+        for (int64_t t = 0; t < n; ++t) {
+            float inv_t = (t == 0) ? 0.0f : 1.0f / (float)t;
+            float p_current = (float)skipped * inv_t;
+            float diff = p_current - target;
+            tau = fmaf(eta, diff, tau);
+            int skip = (t >= W) && (s[t] > tau);
+            keep[b * n + t] = (uint8_t)!skip;
+            if (skip)
+                ++skipped;
+            else
+                kept_idx[b * n + kept++] = (int32_t)t;
+        }
+        for (int64_t i = kept; i < n; ++i)
+            kept_idx[b * n + i] = -1;
+        count[b] = (int32_t)kept;
+        tau_out[b] = tau;
+    }
+}
+
 /* One output row of causal softmax attention restricted to the kept tokens: query at kept
  * rank i of (b, hq) attends kept ranks 0..i of kv head hq / (Hq / Hkv).  out: [d]. */
 static void tfo_attend_one(const float *Q, const float *K, const float *V, int64_t Hq,

@@ -312,6 +312,61 @@ def test_select_tie_break_and_nesting():
     assert np.all(oracle.select(S, 0.0, 1)[0] == 1)
 
 
+
+# ------------------------------------------------------------------ online adaptive threshold
+
+def test_online_threshold_golden_worked_example(golden_dir):
+    tab = _load_table(os.path.join(golden_dir, "online_threshold_worked_example.txt"))
+    S = tab[:, 1][None]
+    keep, idx, count, tau = oracle.select_online(S, 0.5, 0.1, 0.5, 1)
+    np.testing.assert_array_equal(keep[0], tab[:, 2].astype(np.uint8))
+    assert count[0] == 2 and list(idx[0]) == [0, 2, -1, -1, -1]
+    assert abs(float(tau[0]) - 23.0 / 60.0) <= 1e-6
+    # the prefix of the run gives the intermediate thresholds
+    for t in range(5):
+        _, _, _, tau_t = oracle.select_online(S[:, :t + 1], 0.5, 0.1, 0.5, 1)
+        assert abs(float(tau_t[0]) - tab[t, 3]) <= 1e-6
+
+
+def test_online_threshold_closed_forms_and_feedback():
+    rng = np.random.default_rng(21)
+    S = rng.uniform(0, 1, (3, 5000)).astype(np.float32)
+    n = S.shape[1]
+    # eta = 0: a fixed threshold, plain comparison after the warm-up
+    for W in (0, 1, 64):
+        keep, idx, count, tau = oracle.select_online(S, 0.3, 0.0, 0.6, W)
+        ref = (S <= np.float32(0.6)) | (np.arange(n) < W)
+        np.testing.assert_array_equal(keep.astype(bool), ref)
+        assert np.all(tau == np.float32(0.6))
+        for b in range(3):
+            assert count[b] == ref[b].sum()
+            np.testing.assert_array_equal(idx[b, :count[b]], np.nonzero(ref[b])[0])
+            assert np.all(idx[b, count[b]:] == -1)
+    # warm-up covering the row: nothing skipped, the threshold still moves: tau0 - eta * r * n
+    keep, _, count, tau = oracle.select_online(S, 0.25, 1e-3, 0.5, n)
+    assert keep.all() and np.all(count == n)
+    np.testing.assert_allclose(tau, 0.5 - 1e-3 * 0.25 * n, rtol=1e-4)
+    # scores that never exceed the threshold: same trajectory, nothing skipped
+    keep, _, _, tau2 = oracle.select_online(np.full((1, n), -5.0), 0.25, 1e-3, 0.5, 1)
+    assert keep.all()
+    np.testing.assert_array_equal(tau2[0], tau[0])
+    # scores that always exceed it (no warm-up): P_current is 1 from the second token on, so
+    # tau = tau0 - eta r + (n - 1) eta (1 - r)
+    keep, _, count, tau3 = oracle.select_online(np.full((1, 2000), 50.0), 0.25, 1e-3, 0.5, 0)
+    assert not keep.any() and count[0] == 0
+    np.testing.assert_allclose(tau3[0], 0.5 - 1e-3 * 0.25 + 1999 * 1e-3 * 0.75, rtol=1e-4)
+    # negative feedback: on exchangeable scores the achieved skip fraction settles at the target
+    for target in (0.25, 0.5, 0.75):
+        keep, _, count, _ = oracle.select_online(S, target, 0.05, 0.5, 16)
+        frac = 1.0 - count / n
+        assert np.all(np.abs(frac - target) <= 0.02), frac
+    # rows are independent
+    k1, i1, c1, t1 = oracle.select_online(S[1:2], 0.5, 0.05, 0.5, 16)
+    kk, ii, cc, tt = oracle.select_online(S, 0.5, 0.05, 0.5, 16)
+    np.testing.assert_array_equal(k1[0], kk[1])
+    assert c1[0] == cc[1] and t1[0] == tt[1]
+
+
 # ------------------------------------------------------------------ attention
 
 def _sdpa(q, k, v, **kw):
