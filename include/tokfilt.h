@@ -144,6 +144,41 @@ tf_status tf_attend(tf_ctx *ctx, const tf_params *p, const void *Q, const void *
                     const void *V, const int32_t *kept_idx, int32_t m, void *O, void *ws,
                     size_t ws_bytes, void *stream);
 
+/* Online decision with an adaptive threshold (Algorithm 1, threshold and skip lines; warm-up
+ * of Section 3.2; feedback rule of Section 3.3, Eq. 4).  The tokens of a batch row are visited
+ * in order; before token t is judged the threshold moves by eta * (P_current - P_target), where
+ * P_target = p->prune_ratio and P_current is the fraction of the t tokens seen so far that were
+ * skipped; the first p->warmup tokens update the threshold but are never skipped; after that
+ * token t is skipped iff fused[t] > tau.  (Eq. 4's sign: the threshold rises when too much has
+ * been skipped; Algorithm 1 prints the opposite sign.)  Arithmetic, fixed so that results are
+ * reproducible bit for bit: float; P_current = (float)skipped * (1.0f / (float)t) (0 for t = 0);
+ * tau = fmaf(eta, P_current - P_target, tau), starting from tau0.  The kept count is whatever the
+ * controller produces, one per batch row.
+ *   fused     in  [batch][seq] float
+ *   keep      out [batch][seq] u8
+ *   kept_idx  out [batch][seq] int32: the first count[b] entries of row b are the kept positions
+ *                 ascending, the rest is -1
+ *   count     out [batch] int32
+ *   tau       out [batch] float (optional): the threshold the last token was judged with */
+tf_status tf_select_online(tf_ctx *ctx, const tf_params *p, float eta, float tau0,
+                           const float *fused, uint8_t *keep, int32_t *kept_idx, int32_t *count,
+                           float *tau, void *ws, size_t ws_bytes, void *stream);
+
+/* tf_attend for kept sets whose size differs from row to row: kept_idx is [batch][seq], row b
+ * holds count[b] strictly ascending positions (what follows them is not read); count is a
+ * DEVICE array [batch], 0 <= count[b] <= seq.  A row with count 0 gets an all-zero output. */
+tf_status tf_attend_ragged(tf_ctx *ctx, const tf_params *p, const void *Q, const void *K,
+                           const void *V, const int32_t *kept_idx, const int32_t *count, void *O,
+                           void *ws, size_t ws_bytes, void *stream);
+
+/* The whole path with the online decision: tf_score -> tf_select_online -> tf_attend_ragged on
+ * one stream, no host round trip.  Outputs as in those calls; tau may be NULL. */
+tf_status tf_filtered_attention_online(tf_ctx *ctx, const tf_params *p, float eta, float tau0,
+                                       const void *Q, const void *K, const void *V,
+                                       uint8_t *keep, int32_t *kept_idx, int32_t *count,
+                                       float *fused, float *tau, void *O, void *ws,
+                                       size_t ws_bytes, void *stream);
+
 /* The whole path: tf_score -> tf_select -> tf_attend on one stream, no host round trip.
  * Outputs as in the three calls above; tau may be NULL. */
 tf_status tf_filtered_attention(tf_ctx *ctx, const tf_params *p, const void *Q, const void *K,

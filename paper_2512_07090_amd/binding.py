@@ -26,7 +26,8 @@ STAGE_NAMES = ("score", "fuse", "select", "compact", "zero_rows", "attend")
 EXPORTS = ("tf_create", "tf_destroy", "tf_status_string", "tf_last_error", "tf_keep_count",
            "tf_workspace_bytes", "tf_score", "tf_select", "tf_attend", "tf_filtered_attention",
            "tf_stage_timing_enable", "tf_stage_timing_read", "tf_probe_hbm_read",
-           "tf_probe_mfma_bf16", "tf_tail_schedule", "tf_filtered_attention_layers")
+           "tf_probe_mfma_bf16", "tf_tail_schedule", "tf_filtered_attention_layers",
+           "tf_select_online", "tf_attend_ragged", "tf_filtered_attention_online")
 
 
 class tf_params(ctypes.Structure):
@@ -77,6 +78,12 @@ def lib():
         L.tf_filtered_attention.argtypes = [vp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.tf_stage_timing_enable.argtypes = [vp, ctypes.c_int]
         L.tf_stage_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+        flt = ctypes.c_float
+        L.tf_select_online.argtypes = [vp, pp, flt, flt, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.tf_attend_ragged.argtypes = [vp, pp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.tf_filtered_attention_online.argtypes = [vp, pp, flt, flt] + [vp] * 10 + [sz, vp]
+        for name in ("tf_select_online", "tf_attend_ragged", "tf_filtered_attention_online"):
+            getattr(L, name).restype = ctypes.c_int
         dp = ctypes.POINTER(ctypes.c_double)
         vpp = ctypes.POINTER(vp)
         L.tf_tail_schedule.argtypes = [i32, ctypes.c_double, ctypes.c_double, dp, ctypes.POINTER(i32)]
@@ -199,6 +206,25 @@ class Context:
         self._check(lib().tf_filtered_attention(
             self._h, ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(keep), _ptr(kept_idx),
             _ptr(fused), _ptr(tau), _ptr(O), _ptr(ws),
+            0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
+
+    def tf_select_online(self, p, eta, tau0, fused, keep, kept_idx, count, tau, ws, stream=None):
+        self._check(lib().tf_select_online(
+            self._h, ctypes.byref(p), float(eta), float(tau0), _ptr(fused), _ptr(keep),
+            _ptr(kept_idx), _ptr(count), _ptr(tau), _ptr(ws),
+            0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
+
+    def tf_attend_ragged(self, p, Q, K, V, kept_idx, count, O, ws, stream=None):
+        self._check(lib().tf_attend_ragged(
+            self._h, ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(kept_idx), _ptr(count),
+            _ptr(O), _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(),
+            _stream(stream)))
+
+    def tf_filtered_attention_online(self, p, eta, tau0, Q, K, V, keep, kept_idx, count, fused,
+                                     tau, O, ws, stream=None):
+        self._check(lib().tf_filtered_attention_online(
+            self._h, ctypes.byref(p), float(eta), float(tau0), _ptr(Q), _ptr(K), _ptr(V),
+            _ptr(keep), _ptr(kept_idx), _ptr(count), _ptr(fused), _ptr(tau), _ptr(O), _ptr(ws),
             0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
 
     def tf_filtered_attention_layers(self, p, ratios, Q, K, V, keep, kept_idx, fused, tau, O, ws,

@@ -117,7 +117,8 @@ template <int U>
 __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
     Dims d, float scale_log2, int n_qt, int cu_per_xcd, const uint16_t* __restrict__ Q,
     const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
-    const int32_t* __restrict__ kept_idx, uint16_t* __restrict__ O)
+    const int32_t* __restrict__ kept_idx, uint16_t* __restrict__ O,
+    const int32_t* __restrict__ counts, long long idx_stride)
 {
     constexpr int NT = 512 / U;    // threads
     constexpr int CH = 1024 / NT;  // 16-byte chunks per thread per tensor per tile
@@ -148,17 +149,32 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
     const int n_pairs = (n_qt + 1) >> 1;
     const int n_entries = ng * n_pairs;
 
+    // Ragged rows (counts != null: every batch row has its own number of kept tokens, n_qt is
+    // the bound for the longest possible row): entries are listed pair-major, (pair p of group
+    // 0, pair p of group 1, ...), and an entry whose pair lies past the end of its row is empty.
     for (int it = 0;; ++it) {
     const int e = j + (it >> 1) * nwx;
     if (e >= n_entries) break;
-    const int pr = e % n_pairs;
-    const int bh = g_lo + e / n_pairs;
-    const int qt = (it & 1) ? pr : n_qt - 1 - pr;
-    if ((it & 1) && pr == n_qt - 1 - pr) continue;  // the middle tile of an odd count is alone
+    const int pr = counts ? e / ng : e % n_pairs;
+    const int bh = g_lo + (counts ? e % ng : e / n_pairs);
     const int b = bh / d.Hq, hq = bh % d.Hq;
     const int hk = hq / (d.Hq / d.Hkv);
+    const int m = counts ? __builtin_amdgcn_readfirstlane(counts[b]) : d.m;  // kept tokens of this row
+    const int nq = counts ? (m + kBM - 1) / kBM : n_qt;                       // its query tiles
+    if (m == 0) {
+        // a row without kept tokens: nothing attends, every output row is zero
+        if (pr == 0 && !(it & 1)) {
+            uint16_t* Oz = O + (long long)b * d.os[0] + (long long)hq * d.os[1] + 8 * (tid & 15);
+            for (int g = tid >> 4; g < d.n; g += NT / 16)
+                *reinterpret_cast<uint4*>(Oz + (long long)g * d.os[2]) = make_uint4(0, 0, 0, 0);
+        }
+        continue;
+    }
+    if (pr >= (nq + 1) >> 1) continue;
+    const int qt = (it & 1) ? pr : nq - 1 - pr;
+    if ((it & 1) && pr == nq - 1 - pr) continue;  // the middle tile of an odd count is alone
 
-    const int32_t* idx = kept_idx + (long long)b * d.m;
+    const int32_t* idx = kept_idx + (long long)b * idx_stride;
     const uint16_t* Qb = Q + (long long)b * d.qs[0] + (long long)hq * d.qs[1];
     const uint16_t* Kb = K + (long long)b * d.kvs[0] + (long long)hk * d.kvs[1];
     const uint16_t* Vb = V + (long long)b * d.kvs[0] + (long long)hk * d.kvs[1];
@@ -174,9 +190,9 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
     constexpr int NWV = NT / 64;
     const int blk = wave < NWV / 2 ? wave : NWV + NWV / 2 - 1 - wave;
     const int iw = i0 + WQ * blk;    // first query rank of this wave
-    const int i_last = min(i0 + kBM, d.m) - 1;
+    const int i_last = min(i0 + kBM, m) - 1;
     const int n_kt = i_last / kBN + 1;
-    const int m_last = d.m - 1;
+    const int m_last = m - 1;
     // last key rank each of this lane's queries (one per sub-tile) may see
     int lim[U];
 #pragma unroll
@@ -345,7 +361,7 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
 
     // ---- prologue, part 2: scores of step 0; K fragments of step 1 ------------------------
     {
-        const bool diag0 = kBN > iw || kBN > d.m;
+        const bool diag0 = kBN > iw || kBN > m;
         read_kf(k_lds);
         TF_QK(s_x);
 #pragma unroll
@@ -370,8 +386,8 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
         if (j0 <= iw) {                                                                        \
             const uint16_t* vs = v_lds + cur * kVTile;                                         \
             const uint16_t* kn = k_lds + (cur ^ 1) * kKTile;         /* K(kt + 1) */           \
-            const bool m1 = j0 + kBN > iw || j0 + kBN > d.m;         /* this tile is masked */ \
-            const bool m2 = j0 + 2 * kBN > iw || j0 + 2 * kBN > d.m; /* the next one is */     \
+            const bool m1 = j0 + kBN > iw || j0 + kBN > m;           /* this tile is masked */ \
+            const bool m2 = j0 + 2 * kBN > iw || j0 + 2 * kBN > m;   /* the next one is */     \
             TF_STEP(s_x, s_y, vs, kn, j0 + 32, m1);                                            \
             TF_STEP(s_y, s_x, vs + 32 * kVStr, kn + 32 * kKStr, j0 + kBN, m2);                 \
         }                                                                                      \
@@ -434,7 +450,7 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
             const int r = 4 * it + (ln >> 4);  // query row inside the sub-tile
             const int p = __shfl(qpos[u], r);    // its position, held by lane r
             const int pn = __shfl(qnext[u], r);
-            if (iw + 32 * u + r < d.m) {
+            if (iw + 32 * u + r < m) {
                 const uint4 v = *reinterpret_cast<const uint4*>(os + (32 * u + r) * kOStr + 8 * (ln & 15));
                 *reinterpret_cast<uint4*>(Oc + (long long)p * d.os[2]) = v;
                 const int g_end = min(pn, p + 1 + kShortGap);
@@ -445,7 +461,7 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int z0 = qpos[u] + 1 + kShortGap;
-        unsigned long long todo = __ballot(ln < 32 && iw + 32 * u + ln < d.m && z0 < qnext[u]);
+        unsigned long long todo = __ballot(ln < 32 && iw + 32 * u + ln < m && z0 < qnext[u]);
         while (todo) {
             const int r = __builtin_ctzll(todo);
             todo &= todo - 1;
@@ -467,16 +483,18 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
 
 hipError_t launch_attend_bf16(const Dims& d, float scale, const void* Q, const void* K,
                               const void* V, const int32_t* kept_idx, void* O, int n_cu,
-                              hipStream_t s)
+                              const int32_t* counts, long long idx_stride, hipStream_t s)
 {
     constexpr int U = 1;
+    // with per-row counts d.m is the bound (the longest possible row)
     const int n_qt = (d.m + kBM - 1) / kBM;
     const long long items = (long long)d.B * d.Hq * n_qt;
     // at least eight workgroups: every residue of id % 8 owns a share of the groups
     const int grid = (int)std::max<long long>(8, std::min<long long>(items, std::max(n_cu, 1)));
     attend_bf16_kernel<U><<<dim3(grid), dim3(512 / U), 0, s>>>(
         d, scale * 1.44269504088896340736f, n_qt, std::max(n_cu / 8, 1), (const uint16_t*)Q,
-        (const uint16_t*)K, (const uint16_t*)V, kept_idx, (uint16_t*)O);
+        (const uint16_t*)K, (const uint16_t*)V, kept_idx, (uint16_t*)O, counts,
+        counts ? idx_stride : (long long)d.m);
     return hipGetLastError();
 }
 

@@ -39,7 +39,9 @@ __global__ __launch_bounds__(256) void attend_f32_kernel(Dims d, float scale,
                                                          const float* __restrict__ K,
                                                          const float* __restrict__ V,
                                                          const int32_t* __restrict__ kept_idx,
-                                                         float* __restrict__ O)
+                                                         float* __restrict__ O,
+                                                         const int32_t* __restrict__ counts,
+                                                         long long idx_stride)
 {
     __shared__ float Qs[kFM][kFStride];
     __shared__ float Ks[kFN][kFStride];
@@ -48,7 +50,10 @@ __global__ __launch_bounds__(256) void attend_f32_kernel(Dims d, float scale,
 
     const int qt = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
     const int hk = hq / (d.Hq / d.Hkv);
-    const int32_t* idx = kept_idx + (long long)b * d.m;
+    // kept tokens of this batch row (per row when counts is given: d.m is then the bound)
+    const int m = counts ? counts[b] : d.m;
+    if (blockIdx.x * kFM >= m) return;
+    const int32_t* idx = kept_idx + (long long)b * idx_stride;
     const float* Qb = Q + (long long)b * d.qs[0] + (long long)hq * d.qs[1];
     const float* Kb = K + (long long)b * d.kvs[0] + (long long)hk * d.kvs[1];
     const float* Vb = V + (long long)b * d.kvs[0] + (long long)hk * d.kvs[1];
@@ -58,7 +63,7 @@ __global__ __launch_bounds__(256) void attend_f32_kernel(Dims d, float scale,
     const int i = i0 + row;                 // this thread's query rank
 
     {
-        const bool ok = i < d.m;
+        const bool ok = i < m;
         const float* src = ok ? Qb + (long long)idx[i] * d.qs[2] : Qb;
 #pragma unroll
         for (int c4 = 0; c4 < 4; ++c4) {
@@ -78,7 +83,7 @@ __global__ __launch_bounds__(256) void attend_f32_kernel(Dims d, float scale,
         __syncthreads();
         {
             const int j = j0 + row;
-            const bool ok = j < d.m;
+            const bool ok = j < m;
             const long long p = ok ? idx[j] : 0;
 #pragma unroll
             for (int c4 = 0; c4 < 4; ++c4) {
@@ -104,7 +109,7 @@ __global__ __launch_bounds__(256) void attend_f32_kernel(Dims d, float scale,
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             const int j = j0 + g + 8 * kk;
-            s[kk] = (j <= i && j < d.m) ? s[kk] * scale : -1e30f;
+            s[kk] = (j <= i && j < m) ? s[kk] * scale : -1e30f;
             mx = fmaxf(mx, s[kk]);
         }
         mx = fmaxf(mx, __shfl_xor(mx, 1));
@@ -140,7 +145,7 @@ __global__ __launch_bounds__(256) void attend_f32_kernel(Dims d, float scale,
             }
         }
     }
-    if (i < d.m) {
+    if (i < m) {
         float* dst = O + (long long)b * d.os[0] + (long long)hq * d.os[1] + (long long)idx[i] * d.os[2];
         const float inv = 1.0f / l_run;
 #pragma unroll
@@ -164,10 +169,12 @@ hipError_t launch_zero_filtered(const Dims& d, int dtype, const uint8_t* keep, v
 }
 
 hipError_t launch_attend_f32(const Dims& d, float scale, const float* Q, const float* K,
-                             const float* V, const int32_t* kept_idx, float* O, hipStream_t s)
+                             const float* V, const int32_t* kept_idx, float* O,
+                             const int32_t* counts, long long idx_stride, hipStream_t s)
 {
     dim3 grid((d.m + kFM - 1) / kFM, d.Hq, d.B);
-    attend_f32_kernel<<<grid, dim3(256), 0, s>>>(d, scale, Q, K, V, kept_idx, O);
+    attend_f32_kernel<<<grid, dim3(256), 0, s>>>(d, scale, Q, K, V, kept_idx, O, counts,
+                                                 counts ? idx_stride : (long long)d.m);
     return hipGetLastError();
 }
 

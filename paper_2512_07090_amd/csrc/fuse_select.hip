@@ -309,13 +309,90 @@ __global__ __launch_bounds__(kSelThreads) void select_compact_kernel(
     }
 }
 
+// ------------------------------------------------------------------------------ online decision
+// Adaptive threshold (Algorithm 1 threshold / skip lines, warm-up of Section 3.2, Eq. 4): a
+// sequential recurrence over a row's tokens,
+//   tau <- fma(eta, (float)skipped * (1 / t) - target, tau);  skip iff t >= W and S_t > tau,
+// all in float so that the result is reproducible bit for bit.  One workgroup per batch row
+// walks the row in chunks of kOnChunk tokens: all threads stage the chunk's scores and the
+// reciprocals 1 / t in LDS, thread 0 runs the recurrence (both candidates of the next threshold,
+// for "skipped" and "kept", are formed next to the comparison, so that the chain from one token
+// to the next is a compare and a select), then all threads compact the chunk's flags.
+constexpr int kOnChunk = 4096;
+
+__global__ __launch_bounds__(kSelThreads) void select_online_kernel(
+    const float* __restrict__ fused, int n, int warmup, float target, float eta, float tau0,
+    uint8_t* __restrict__ keep, int32_t* __restrict__ kept_idx, int32_t* __restrict__ count,
+    float* __restrict__ tau_out)
+{
+    // every product and difference below is rounded on its own (the only fused operations are
+    // the fmaf calls): the recurrence is defined operation by operation
+#pragma clang fp contract(off)
+    __shared__ float s_lds[kOnChunk];
+    __shared__ float inv_lds[kOnChunk];
+    __shared__ uint8_t flag_lds[kOnChunk];
+    __shared__ int scan_lds[kSelWaves + 1];
+
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x;
+    const float* S = fused + (long long)b * n;
+    uint8_t* kp = keep + (long long)b * n;
+    int32_t* out = kept_idx + (long long)b * n;
+
+    // state of the recurrence (meaningful in thread 0): tau is the threshold token t0 of the
+    // next chunk will be judged with, already updated for it
+    float skipped = 0.f;  // exact in float up to 2^24 tokens
+    float tau = fmaf(eta, 0.f - target, tau0);
+    float tau_judged = tau;  // the threshold the latest token was judged with
+    int base = 0;            // kept tokens so far
+    for (int t0 = 0; t0 < n; t0 += kOnChunk) {
+        const int len = min(kOnChunk, n - t0);
+        for (int i = tid; i < len; i += kSelThreads) s_lds[i] = S[t0 + i];
+        // reciprocal of the NEXT token's index: inv_lds[i] = 1 / (t0 + i + 1)
+        for (int i = tid; i < len; i += kSelThreads) inv_lds[i] = 1.0f / (float)(t0 + i + 1);
+        __syncthreads();
+        if (tid == 0) {
+            for (int i = 0; i < len; ++i) {
+                const int t = t0 + i;
+                // thresholds of token t + 1 for both outcomes of token t
+                const float inv_n = inv_lds[i];
+                const float p_k = skipped * inv_n, p_s = (skipped + 1.f) * inv_n;
+                const float tau_k = fmaf(eta, p_k - target, tau);
+                const float tau_s = fmaf(eta, p_s - target, tau);
+                const bool skip = t >= warmup && s_lds[i] > tau;
+                flag_lds[i] = skip ? 0 : 1;
+                tau_judged = tau;
+                tau = skip ? tau_s : tau_k;
+                skipped = skip ? skipped + 1.f : skipped;
+            }
+        }
+        __syncthreads();
+        for (int i0 = 0; i0 < len; i0 += kSelThreads) {
+            const int i = i0 + tid;
+            const int flag = i < len ? flag_lds[i] : 0;
+            int total;
+            const int pos = base + block_excl_scan(flag, scan_lds, &total);
+            base += total;
+            if (i < len) kp[t0 + i] = (uint8_t)flag;
+            if (flag) out[pos] = t0 + i;
+        }
+        __syncthreads();
+    }
+    for (int i = base + tid; i < n; i += kSelThreads) out[i] = -1;
+    if (tid == 0) {
+        count[b] = base;
+        if (tau_out) tau_out[b] = tau_judged;
+    }
+}
+
 __global__ void mask_from_idx_kernel(const int32_t* __restrict__ kept_idx, int n, int m,
-                                     uint8_t* __restrict__ keep)
+                                     uint8_t* __restrict__ keep,
+                                     const int32_t* __restrict__ counts, long long idx_stride)
 {
     const int b = blockIdx.y;
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < m) {
-        const int p = kept_idx[(long long)b * m + i];
+    if (i < (counts ? counts[b] : m)) {
+        const int p = kept_idx[(long long)b * idx_stride + i];
         if (p >= 0 && p < n) keep[(long long)b * n + p] = 1;
     }
 }
@@ -362,6 +439,15 @@ hipError_t launch_select_compact(const Dims& d, int warmup, const float* fused, 
     return hipGetLastError();
 }
 
+hipError_t launch_select_online(const Dims& d, int warmup, float target, float eta, float tau0,
+                                const float* fused, uint8_t* keep, int32_t* kept_idx,
+                                int32_t* count, float* tau, hipStream_t s)
+{
+    select_online_kernel<<<dim3(d.B), dim3(kSelThreads), 0, s>>>(fused, d.n, warmup, target, eta,
+                                                                 tau0, keep, kept_idx, count, tau);
+    return hipGetLastError();
+}
+
 hipError_t launch_compact(const Dims& d, const uint8_t* keep, int32_t* kept_idx, hipStream_t s)
 {
     compact_kernel<<<dim3(d.B), dim3(kSelThreads), 0, s>>>(keep, d.n, d.m, kept_idx);
@@ -388,12 +474,12 @@ hipError_t launch_keep_all(const Dims& d, uint8_t* keep, int32_t* kept_idx, floa
 }
 
 hipError_t launch_mask_from_idx(const Dims& d, const int32_t* kept_idx, uint8_t* keep,
-                                hipStream_t s)
+                                const int32_t* counts, long long idx_stride, hipStream_t s)
 {
     const long long count = (long long)d.B * d.n;
     clear_bytes_kernel<<<dim3((unsigned)((count + 255) / 256)), dim3(256), 0, s>>>(keep, count);
-    mask_from_idx_kernel<<<dim3((d.m + 255) / 256, d.B), dim3(256), 0, s>>>(kept_idx, d.n, d.m,
-                                                                           keep);
+    mask_from_idx_kernel<<<dim3((d.m + 255) / 256, d.B), dim3(256), 0, s>>>(
+        kept_idx, d.n, d.m, keep, counts, counts ? idx_stride : (long long)d.m);
     return hipGetLastError();
 }
 

@@ -44,23 +44,31 @@ hipError_t launch_compact(const Dims& d, const uint8_t* keep, int32_t* kept_idx,
 // kernels above)
 hipError_t launch_select_compact(const Dims& d, int warmup, const float* fused, uint8_t* keep,
                                  int32_t* kept_idx, float* tau, hipStream_t s);
+// online decision with an adaptive threshold: keep [B][n], kept_idx [B][n] (kept positions
+// ascending, then -1), count [B], tau [B] (may be null)
+hipError_t launch_select_online(const Dims& d, int warmup, float target, float eta, float tau0,
+                                const float* fused, uint8_t* keep, int32_t* kept_idx,
+                                int32_t* count, float* tau, hipStream_t s);
 // every token kept: keep = 1, kept_idx = 0 .. n-1, tau = +inf (tau may be null)
 hipError_t launch_keep_all(const Dims& d, uint8_t* keep, int32_t* kept_idx, float* tau,
                            hipStream_t s);
 // keep mask from an index list (for callers that bring their own kept set)
 hipError_t launch_mask_from_idx(const Dims& d, const int32_t* kept_idx, uint8_t* keep,
-                                hipStream_t s);
+                                const int32_t* counts, long long idx_stride, hipStream_t s);
 
 // ---- attention over the kept tokens -------------------------------------------------------
 hipError_t launch_zero_filtered(const Dims& d, int dtype, const uint8_t* keep, void* O,
                                 hipStream_t s);
+// counts (may be null): per-row numbers of kept tokens [B]; kept_idx rows are then idx_stride
+// apart and d.m is only the bound on a row's count
 hipError_t launch_attend_f32(const Dims& d, float scale, const float* Q, const float* K,
-                             const float* V, const int32_t* kept_idx, float* O, hipStream_t s);
+                             const float* V, const int32_t* kept_idx, float* O,
+                             const int32_t* counts, long long idx_stride, hipStream_t s);
 // also writes the zero rows of filtered positions (kept_idx strictly ascending).  n_cu: compute
 // units of the device (one persistent workgroup each).
 hipError_t launch_attend_bf16(const Dims& d, float scale, const void* Q, const void* K,
                               const void* V, const int32_t* kept_idx, void* O, int n_cu,
-                              hipStream_t s);
+                              const int32_t* counts, long long idx_stride, hipStream_t s);
 
 // ---- measurement probes (not part of the path) ---------------------------------------------
 hipError_t launch_probe_stream_read(const void* src, size_t bytes, void* sink, int n_cu,

@@ -139,9 +139,12 @@ void mark(tf_ctx* ctx, int slot, int stage, hipStream_t s)
     if (slot >= 0) (void)hipEventRecord(ctx->ev[slot][stage], s);
 }
 
+// counts (may be null): per-row kept counts on the device; kept_idx rows are then p->seq apart
+// and d.m is the bound p->seq
 tf_status run_attend(tf_ctx* ctx, const tf_params* p, const tf::Dims& d, const void* Q,
                      const void* K, const void* V, const int32_t* kept_idx,
-                     const uint8_t* keep, void* O, hipStream_t s, int slot)
+                     const uint8_t* keep, void* O, hipStream_t s, int slot,
+                     const int32_t* counts = nullptr)
 {
     const float scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
     if (p->dtype == TF_F32) {
@@ -149,11 +152,11 @@ tf_status run_attend(tf_ctx* ctx, const tf_params* p, const tf::Dims& d, const v
         if (st != TF_OK) return st;
         mark(ctx, slot, TF_STAGE_ATTEND, s);
         return dev(ctx, tf::launch_attend_f32(d, scale, (const float*)Q, (const float*)K, (const float*)V,
-                                              kept_idx, (float*)O, s), "fp32 attention launch");
+                                              kept_idx, (float*)O, counts, p->seq, s), "fp32 attention launch");
     }
     // the bf16 kernel writes the zero rows itself
     mark(ctx, slot, TF_STAGE_ATTEND, s);
-    return dev(ctx, tf::launch_attend_bf16(d, scale, Q, K, V, kept_idx, O, ctx->n_cu, s),
+    return dev(ctx, tf::launch_attend_bf16(d, scale, Q, K, V, kept_idx, O, ctx->n_cu, counts, p->seq, s),
                "bf16 attention launch");
 }
 
@@ -319,10 +322,78 @@ tf_status tf_attend(tf_ctx* ctx, const tf_params* p, const void* Q, const void* 
     hipStream_t s = (hipStream_t)stream;
     uint8_t* keep = (uint8_t*)((char*)ws + w.keep_tmp);
     if (p->dtype == TF_F32) {  // the fp32 path zero-fills from a mask
-        st = dev(ctx, tf::launch_mask_from_idx(d, kept_idx, keep, s), "mask launch");
+        st = dev(ctx, tf::launch_mask_from_idx(d, kept_idx, keep, nullptr, 0, s), "mask launch");
         if (st != TF_OK) return st;
     }
     return run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, s, -1);
+}
+
+tf_status tf_select_online(tf_ctx* ctx, const tf_params* p, float eta, float tau0,
+                           const float* fused, uint8_t* keep, int32_t* kept_idx, int32_t* count,
+                           float* tau, void* ws, size_t ws_bytes, void* stream)
+{
+    Workspace w;
+    tf_status st = enter(ctx, p, ws, ws_bytes, &w);
+    if (st != TF_OK) return st;
+    if (!fused || !keep || !kept_idx || !count)
+        return fail(ctx, TF_ERR_INVALID_ARG, "fused, keep, kept_idx and count must not be NULL");
+    if (!(eta >= 0.f) || isinf(eta) || isnan(tau0) || isinf(tau0))
+        return fail(ctx, TF_ERR_INVALID_ARG, "eta must be finite and >= 0, tau0 finite");
+    const tf::Dims d = make_dims(p, p->seq);
+    return dev(ctx, tf::launch_select_online(d, p->warmup, (float)p->prune_ratio, eta, tau0, fused, keep,
+                                             kept_idx, count, tau, (hipStream_t)stream),
+               "online decision launch");
+}
+
+tf_status tf_attend_ragged(tf_ctx* ctx, const tf_params* p, const void* Q, const void* K,
+                           const void* V, const int32_t* kept_idx, const int32_t* count, void* O,
+                           void* ws, size_t ws_bytes, void* stream)
+{
+    Workspace w;
+    tf_status st = enter(ctx, p, ws, ws_bytes, &w);
+    if (st != TF_OK) return st;
+    if (!Q || !K || !V || !O || !kept_idx || !count)
+        return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V, O, kept_idx and count must not be NULL");
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O))
+        return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V and O must be 16-byte aligned");
+    const tf::Dims d = make_dims(p, p->seq);
+    hipStream_t s = (hipStream_t)stream;
+    uint8_t* keep = (uint8_t*)((char*)ws + w.keep_tmp);
+    if (p->dtype == TF_F32) {  // the fp32 path zero-fills from a mask
+        st = dev(ctx, tf::launch_mask_from_idx(d, kept_idx, keep, count, p->seq, s), "mask launch");
+        if (st != TF_OK) return st;
+    }
+    return run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, s, -1, count);
+}
+
+tf_status tf_filtered_attention_online(tf_ctx* ctx, const tf_params* p, float eta, float tau0,
+                                       const void* Q, const void* K, const void* V, uint8_t* keep,
+                                       int32_t* kept_idx, int32_t* count, float* fused, float* tau,
+                                       void* O, void* ws, size_t ws_bytes, void* stream)
+{
+    Workspace w;
+    tf_status st = enter(ctx, p, ws, ws_bytes, &w);
+    if (st != TF_OK) return st;
+    if (!Q || !K || !V || !O || !keep || !kept_idx || !count || !fused)
+        return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V, O, keep, kept_idx, count and fused must not be NULL");
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O))
+        return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V and O must be 16-byte aligned");
+    if (!(eta >= 0.f) || isinf(eta) || isnan(tau0) || isinf(tau0))
+        return fail(ctx, TF_ERR_INVALID_ARG, "eta must be finite and >= 0, tau0 finite");
+    const tf::Dims d = make_dims(p, p->seq);
+    hipStream_t s = (hipStream_t)stream;
+    char* base = (char*)ws;
+    float* sk = (float*)(base + w.sim_k);
+    float* sv = (float*)(base + w.sim_v);
+    st = dev(ctx, tf::launch_score(d, p->dtype, K, V, sk, sv, (float*)(base + w.seg_tot),
+                                   score_tensors(p), p->anchor, p->ema_gamma, s), "score launch");
+    if (st != TF_OK) return st;
+    st = dev(ctx, tf::launch_fuse(d, p->fusion, sk, sv, fused, s), "fuse launch");
+    if (st != TF_OK) return st;
+    st = dev(ctx, tf::launch_select_online(d, p->warmup, (float)p->prune_ratio, eta, tau0, fused, keep,
+                                           kept_idx, count, tau, s), "online decision launch");
+    if (st != TF_OK) return st;
+    return run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, s, -1, count);
 }
 
 tf_status tf_filtered_attention(tf_ctx* ctx, const tf_params* p, const void* Q, const void* K,

@@ -570,3 +570,103 @@ def test_tail_focused_layers_match_the_oracle_layer_by_layer(ctx, dt):
             p, [0.0, 0.0, 0.5, 1.0], [d_[0] for d_ in dev], [d_[1] for d_ in dev],
             [d_[2] for d_ in dev], [b_.keep for b_ in bufs], [b_.kept_idx for b_ in bufs],
             [b_.fused for b_ in bufs], None, [b_.O for b_ in bufs], bufs[0].ws)
+
+
+# ------------------------------------------------------------------ online decision, ragged rows
+
+@pytest.mark.parametrize("case", [
+    # (B, n, target, eta, tau0, W)
+    (1, 5, 0.5, 0.1, 0.5, 1), (3, 1000, 0.5, 0.05, 0.5, 16), (2, 4096, 0.25, 0.01, 0.9, 1),
+    (2, 10000, 0.75, 0.05, 0.1, 64), (1, 4097, 0.5, 0.0, 0.6, 0), (2, 300, 0.5, 0.2, -5.0, 0),
+    (1, 1, 0.5, 0.1, 0.5, 1), (1, 20000, 0.5, 1e-3, 0.5, 1), (4, 777, 0.9, 0.3, 2.0, 5),
+])
+def test_select_online_bit_exact_on_identical_scores(ctx, case):
+    """The threshold recurrence is defined operation by operation in float, so the kernel must
+    reproduce the oracle's mask, indices, counts and final threshold exactly."""
+    Bn, n, target, eta, tau0, W = case
+    _say("select online %s" % (case,))
+    rng = np.random.default_rng(n + Bn)
+    S = rng.uniform(0, 1, (Bn, n)).astype(np.float32)
+    if n > 10:
+        S[0, 3:9] = 0.5                                   # ties with a round threshold
+    keep_r, idx_r, cnt_r, tau_r = oracle.select_online(S, target, eta, tau0, W)
+    p = B.make_params((Bn, 1, n, 128), (Bn, 1, n, 128), torch.float32, target, W)
+    keep = torch.zeros((Bn, n), dtype=torch.uint8, device="cuda:0")
+    idx = torch.full((Bn, n), -7, dtype=torch.int32, device="cuda:0")
+    cnt = torch.zeros((Bn,), dtype=torch.int32, device="cuda:0")
+    tau = torch.zeros((Bn,), dtype=torch.float32, device="cuda:0")
+    ws = torch.empty(B.tf_workspace_bytes(p), dtype=torch.uint8, device="cuda:0")
+    ctx.tf_select_online(p, eta, tau0, torch.from_numpy(S).cuda(), keep, idx, cnt, tau, ws)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(keep.cpu().numpy(), keep_r)
+    np.testing.assert_array_equal(idx.cpu().numpy(), idx_r)
+    np.testing.assert_array_equal(cnt.cpu().numpy(), cnt_r)
+    np.testing.assert_array_equal(tau.cpu().numpy(), tau_r)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_attend_ragged_rows(ctx, dt):
+    """Kept sets of different sizes per batch row: none, one token, one query tile exactly, a
+    ragged count, everything."""
+    _say("attend ragged %s" % dt)
+    n = 1200
+    counts = [0, 1, 256, 777, n]
+    Bn = len(counts)
+    q, k, v, _ = synth.make_random_qkv(Bn, 4, 2, n, 128, dtype=dt, seed=55)
+    rng = np.random.default_rng(9)
+    idx = np.full((Bn, n), 123456, dtype=np.int32)        # what follows a row's entries is never read
+    for b, c in enumerate(counts):
+        idx[b, :c] = np.sort(rng.choice(n, c, replace=False))
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.5)
+    buf = B.Buffers(p, "cuda:0")
+    buf.O.fill_(float("nan"))
+    ctx.tf_attend_ragged(p, q.cuda(), k.cuda(), v.cuda(), torch.from_numpy(idx).cuda(),
+                         torch.tensor(counts, dtype=torch.int32, device="cuda:0"), buf.O, buf.ws)
+    torch.cuda.synchronize()
+    O_g = buf.O.float().cpu().numpy().astype(np.float64)
+    assert not np.isnan(O_g).any()
+    for b, c in enumerate(counts):
+        if c == 0:
+            assert np.all(O_g[b] == 0)
+            continue
+        ref = oracle.attend(q[b:b + 1], k[b:b + 1], v[b:b + 1], idx[b:b + 1, :c])
+        assert np.abs(O_g[b] - ref[0]).max() <= ATTN_TOL[q.dtype], "row %d" % b
+        filtered = np.setdiff1d(np.arange(n), idx[b, :c])
+        assert np.all(O_g[b][:, filtered] == 0)
+
+
+@pytest.mark.parametrize("wl", [0, 1])
+def test_whole_path_online_threshold(ctx, wl):
+    _say("whole path online cfg%d" % (wl + 1))
+    w = synth.workload(wl)
+    if wl == 1:
+        w = synth.scaled(w, batch=2, seq=2500, n_q_heads=8, n_kv_heads=8)
+    q, k, v, _ = synth.make_qkv(w)
+    target, eta, tau0, W = 0.5, 0.02, 0.5, 8
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, target, W)
+    Bn, n = q.shape[0], q.shape[2]
+    buf = B.Buffers(p, "cuda:0")
+    idx = torch.full((Bn, n), -7, dtype=torch.int32, device="cuda:0")
+    cnt = torch.zeros((Bn,), dtype=torch.int32, device="cuda:0")
+    buf.O.fill_(float("nan"))
+    ctx.tf_filtered_attention_online(p, eta, tau0, q.cuda(), k.cuda(), v.cuda(), buf.keep, idx, cnt,
+                                     buf.fused, buf.tau, buf.O, buf.ws)
+    torch.cuda.synchronize()
+    ref = oracle.filtered_attention(q, k, v, target, W, with_attention=False)
+    fused_g = buf.fused.cpu().numpy()
+    assert_scores_close(fused_g, ref["fused"], "fused")
+    # the recurrence is chaotic in its input (one flipped decision moves every later threshold),
+    # so the decision is checked on the kernel's own scores, where it must be exact
+    keep_r, idx_r, cnt_r, tau_r = oracle.select_online(fused_g, target, eta, tau0, W)
+    np.testing.assert_array_equal(buf.keep.cpu().numpy(), keep_r)
+    np.testing.assert_array_equal(idx.cpu().numpy(), idx_r)
+    np.testing.assert_array_equal(cnt.cpu().numpy(), cnt_r)
+    np.testing.assert_array_equal(buf.tau.cpu().numpy(), tau_r)
+    assert np.all(np.abs(1.0 - cnt_r / n - target) <= 0.05)           # the controller holds the budget
+    O_g = buf.O.float().cpu().numpy().astype(np.float64)
+    assert not np.isnan(O_g).any()
+    for b in range(Bn):
+        c = int(cnt_r[b])
+        O_ref = oracle.attend(q[b:b + 1], k[b:b + 1], v[b:b + 1], idx_r[b:b + 1, :c])
+        assert np.abs(O_g[b] - O_ref[0]).max() <= ATTN_TOL[q.dtype]
+        assert np.all(O_g[b][:, keep_r[b] == 0] == 0)
