@@ -214,6 +214,34 @@ def main():
                               "attend_ms": round(st3[5] / max(n3, 1), 4)}
             del b3
 
+        # the online decision (adaptive threshold of Eq. 4) in place of the exact count: whole
+        # path, and the decision kernel alone on the scores of the headline run
+        p4 = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, args.ratio, warmup=8)
+        b4 = B.Buffers(p4, dev)
+        idx4 = torch.empty((w.batch, w.seq), dtype=torch.int32, device=dev)
+        cnt4 = torch.empty((w.batch,), dtype=torch.int32, device=dev)
+
+        def step4():
+            ctx.tf_filtered_attention_online(p4, 0.02, 0.5, qd, kd, vd, b4.keep, idx4, cnt4,
+                                             b4.fused, b4.tau, b4.O, b4.ws)
+
+        def sel4():
+            ctx.tf_select_online(p4, 0.02, 0.5, buf.fused, b4.keep, idx4, cnt4, b4.tau, b4.ws)
+        res4 = []
+        for fn in (step4, sel4):
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(K):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            res4.append(e0.elapsed_time(e1) / K)
+        variants["online_eta_0.02"] = {"ms_per_step": round(res4[0], 4), "select_online_ms": round(res4[1], 4),
+                                       "kept_per_row": [int(x) for x in cnt4.cpu().tolist()]}
+        del b4
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle

@@ -328,9 +328,9 @@ __global__ __launch_bounds__(kSelThreads) void select_online_kernel(
     // every product and difference below is rounded on its own (the only fused operations are
     // the fmaf calls): the recurrence is defined operation by operation
 #pragma clang fp contract(off)
-    __shared__ float s_lds[kOnChunk];
-    __shared__ float inv_lds[kOnChunk];
-    __shared__ uint8_t flag_lds[kOnChunk];
+    __shared__ __attribute__((aligned(16))) float s_lds[kOnChunk];
+    __shared__ __attribute__((aligned(16))) float inv_lds[kOnChunk];
+    __shared__ __attribute__((aligned(16))) uint8_t flag_lds[kOnChunk];
     __shared__ int scan_lds[kSelWaves + 1];
 
     const int b = blockIdx.x;
@@ -347,23 +347,44 @@ __global__ __launch_bounds__(kSelThreads) void select_online_kernel(
     int base = 0;            // kept tokens so far
     for (int t0 = 0; t0 < n; t0 += kOnChunk) {
         const int len = min(kOnChunk, n - t0);
-        for (int i = tid; i < len; i += kSelThreads) s_lds[i] = S[t0 + i];
+        // (warm-up tokens and the padding up to a multiple of 8 get a score that is never above
+        // the threshold, so the chain below needs no test for them)
+        for (int i = tid; i < ((len + 7) & ~7); i += kSelThreads)
+            s_lds[i] = (i < len && t0 + i >= warmup) ? S[t0 + i] : -INFINITY;
         // reciprocal of the NEXT token's index: inv_lds[i] = 1 / (t0 + i + 1)
-        for (int i = tid; i < len; i += kSelThreads) inv_lds[i] = 1.0f / (float)(t0 + i + 1);
+        for (int i = tid; i < ((len + 7) & ~7); i += kSelThreads) inv_lds[i] = 1.0f / (float)(t0 + i + 1);
         __syncthreads();
         if (tid == 0) {
-            for (int i = 0; i < len; ++i) {
-                const int t = t0 + i;
-                // thresholds of token t + 1 for both outcomes of token t
-                const float inv_n = inv_lds[i];
-                const float p_k = skipped * inv_n, p_s = (skipped + 1.f) * inv_n;
-                const float tau_k = fmaf(eta, p_k - target, tau);
-                const float tau_s = fmaf(eta, p_s - target, tau);
-                const bool skip = t >= warmup && s_lds[i] > tau;
-                flag_lds[i] = skip ? 0 : 1;
-                tau_judged = tau;
-                tau = skip ? tau_s : tau_k;
-                skipped = skip ? skipped + 1.f : skipped;
+            // eight tokens at a time: their scores and reciprocals are fetched together (two
+            // 16-byte LDS reads each), the eight steps of the chain then run from registers and
+            // the eight flags leave as one 8-byte store
+            for (int i0 = 0; i0 < len; i0 += 8) {
+                float sv[8], iv[8];
+                *reinterpret_cast<float4*>(&sv[0]) = *reinterpret_cast<const float4*>(&s_lds[i0]);
+                *reinterpret_cast<float4*>(&sv[4]) = *reinterpret_cast<const float4*>(&s_lds[i0 + 4]);
+                *reinterpret_cast<float4*>(&iv[0]) = *reinterpret_cast<const float4*>(&inv_lds[i0]);
+                *reinterpret_cast<float4*>(&iv[4]) = *reinterpret_cast<const float4*>(&inv_lds[i0 + 4]);
+                float tau_in[8];  // the threshold each of the eight tokens is judged with
+                unsigned long long flags = 0;
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    // thresholds of the next token for both outcomes of this one
+                    const float s1 = skipped + 1.f;
+                    const float p_k = skipped * iv[u], p_s = s1 * iv[u];
+                    const float tau_k = fmaf(eta, p_k - target, tau);
+                    const float tau_s = fmaf(eta, p_s - target, tau);
+                    const bool skip = sv[u] > tau;
+                    flags |= (unsigned long long)(skip ? 0 : 1) << (8 * u);
+                    tau_in[u] = tau;
+                    tau = skip ? tau_s : tau_k;
+                    skipped = skip ? s1 : skipped;
+                }
+                *reinterpret_cast<unsigned long long*>(&flag_lds[i0]) = flags;
+                if (i0 + 8 >= len) {  // the group that holds the row's last token
+#pragma unroll
+                    for (int u = 0; u < 8; ++u)
+                        if (t0 + i0 + u == n - 1) tau_judged = tau_in[u];
+                }
             }
         }
         __syncthreads();
