@@ -12,7 +12,7 @@ Prints ONE JSON line.  Besides the whole-path throughput it carries
                 the launch stream inside the timed steps, against the 2.5 PFLOP/s dense bf16
                 peak;
   cpu_baseline  the CPU oracle, as it stands, timed on the host cores over a bounded sample
-                (whole path on one batch row of the same workload);
+                (whole path on the batch rows of the same workload; one row when n > 4096);
   ceilings      what this device reaches on a plain streaming read of the K tensor and on
                 back-to-back bf16 MFMAs (the library's probes), next to the vendor peaks;
   other_ratios  the same workload at the other pruning ratio its configuration names (0.25),
