@@ -51,6 +51,10 @@ def _load():
         lib.tfo_attend.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, vp, i64, dbl, vp]
         lib.tfo_attend_rows.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, vp, i64, dbl,
                                         vp, i64, vp]
+        lib.tfo_decode_step.argtypes = [vp, vp, vp, i64, i64, i64, i64, ctypes.c_int, dbl,
+                                        ctypes.c_int, i64, flt, flt, dbl, vp, vp, vp, vp, vp, vp,
+                                        vp, vp, vp, i64, vp, vp, vp]
+        lib.tfo_decode_step.restype = ctypes.c_int
         _lib = lib
     return _lib
 
@@ -199,3 +203,47 @@ def filtered_attention(q, k, v, ratio: float, warmup: int = 1, mode: int = FUSE_
     if with_attention:
         out["O"] = attend(q, k, v, idx, scale)
     return out
+
+
+class DecodeState:
+    """State of the per-token form of the layer (Algorithm 1 called once per new token): the
+    anchors, the controller's counters and threshold, and the cache of kept keys / values.
+    All arrays are numpy and may be inspected between steps."""
+
+    def __init__(self, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, capacity: int,
+                 target: float, eta: float, tau0: float, warmup: int = 1, mode: int = FUSE_EQ2,
+                 scale: float = 0.0, ema_gamma=None):
+        self.B, self.Hq, self.Hkv, self.d, self.capacity = batch, n_q_heads, n_kv_heads, head_dim, capacity
+        self.target, self.eta, self.warmup, self.mode = float(target), float(eta), int(warmup), int(mode)
+        self.scale = _scale(head_dim, scale)
+        self.ema_gamma = ema_gamma
+        self.anchor_k = np.zeros((batch, n_kv_heads, head_dim), dtype=np.float64)
+        self.anchor_v = np.zeros((batch, n_kv_heads, head_dim), dtype=np.float64)
+        self.seen = np.zeros(batch, dtype=np.int32)
+        self.skipped = np.zeros(batch, dtype=np.int32)
+        self.tau = np.full(batch, tau0, dtype=np.float32)
+        self.cache_len = np.zeros(batch, dtype=np.int32)
+        self.k_cache = np.zeros((batch, n_kv_heads, capacity, head_dim), dtype=np.float32)
+        self.v_cache = np.zeros((batch, n_kv_heads, capacity, head_dim), dtype=np.float32)
+
+    def step(self, q, k, v, decide_on=None):
+        """One new token per batch row.  q: [B, Hq, d]; k, v: [B, Hkv, d].  decide_on: optional
+        [B] float32 scores to decide on instead of the ones computed here.
+        Returns (o [B, Hq, d] float64, skip [B] uint8, fused [B] float64)."""
+        qa, ka, va = _f32(q), _f32(k), _f32(v)
+        assert qa.shape == (self.B, self.Hq, self.d) and ka.shape == va.shape == (self.B, self.Hkv, self.d)
+        o = np.empty((self.B, self.Hq, self.d), dtype=np.float64)
+        skip = np.empty(self.B, dtype=np.uint8)
+        fused = np.empty(self.B, dtype=np.float64)
+        dec = None if decide_on is None else np.ascontiguousarray(decide_on, dtype=np.float32)
+        rc = _load().tfo_decode_step(
+            _p(qa), _p(ka), _p(va), self.B, self.Hq, self.Hkv, self.d,
+            0 if self.ema_gamma is None else 1,
+            0.0 if self.ema_gamma is None else float(self.ema_gamma), self.mode, self.warmup,
+            ctypes.c_float(self.target), ctypes.c_float(self.eta), self.scale,
+            None if dec is None else _p(dec), _p(self.anchor_k), _p(self.anchor_v),
+            _p(self.seen), _p(self.skipped), _p(self.tau), _p(self.cache_len), _p(self.k_cache),
+            _p(self.v_cache), self.capacity, _p(o), _p(skip), _p(fused))
+        if rc != 0:
+            raise OverflowError("decode step: a kept token does not fit the cache")
+        return o, skip, fused

@@ -28,7 +28,10 @@
  *     the lowest score are kept, ties broken towards the lower index, after force-keeping
  *     the first W tokens (warm-up); the decision is taken on the score rounded to float,
  *     the precision the GPU path decides in;
- *   - filtered tokens are neither queries nor keys.
+ *   - filtered tokens are neither queries nor keys;
+ *   - the per-token form (tfo_decode_step) keeps the anchors over ALL earlier tokens, kept or
+ *     skipped (the anchor is the mean of previous keys, not of cached keys), and caches only
+ *     kept tokens; token by token it reproduces the batched functions exactly.
  *
  * Parity pins live in tests/test_oracle_pins.py.  Unpinned by the paper (fixed only by the
  * readings above): fusion direction, warm-up length, the two epsilons, the tie-break.
@@ -385,4 +388,135 @@ void tfo_attend_rows(const float *Q, const float *K, const float *V, int64_t B, 
                        out + r * d);
         free(logits);
     }
+}
+
+/* One decoding step of the Token Filtering layer for every batch row (Algorithm 1 as a per-token
+ * call; anchor of Section 3.2 / Eq. 1; fusion of Eq. 2; warm-up of Section 3.2; threshold rule of
+ * Section 3.3, Eq. 4; zero attention output for a skipped token, Section 3.2).
+ * State carried between calls (all owned by the caller, one entry per batch row unless stated):
+ *   anchor_k, anchor_v [B][Hkv][d] double: anchor kind 0: sums of all rows seen so far (the mean
+ *       is formed when a row is scored); kind 1: the incremental anchors of Eq. 1;
+ *   seen, skipped: tokens seen / skipped so far;  tau: the threshold (float);
+ *   cache_len: rows held in the cache;  k_cache, v_cache [B][Hkv][capacity][d]: keys / values of
+ *       the kept tokens in arrival order.
+ * Steps, in this order: the new key and value are scored against the anchors as they stand (the
+ * anchors never include the current token, and they include every earlier token, kept or not);
+ * the threshold moves exactly as in tfo_select_online (float arithmetic); the token is skipped
+ * iff seen >= W and S > tau (S rounded to float); the anchors absorb the token; a kept token is
+ * appended to the cache and attends over the whole cache, itself included (a skipped token is
+ * neither cached nor attended to, and its output is zero).
+ * decide_on (may be NULL): [B] scores to take the decision on in place of this function's own
+ * (for comparing an implementation whose scores differ in the last bits).
+ * o: [B][Hq][d] double.  skip: [B] 0/1.  fused: [B] double.
+ * Returns 0, or -1 if a kept token does not fit its row's cache (nothing is changed then). */
+int tfo_decode_step(const float *q, const float *k, const float *v, int64_t B, int64_t Hq,
+                    int64_t Hkv, int64_t d, int anchor_kind, double gamma, int fusion, int64_t W,
+                    float target, float eta, double scale, const float *decide_on,
+                    double *anchor_k, double *anchor_v, int32_t *seen, int32_t *skipped,
+                    float *tau, int32_t *cache_len, float *k_cache, float *v_cache,
+                    int64_t capacity, double *o, uint8_t *skip, double *fused)
+{
+    double *ck = (double *)malloc((size_t)(2 * B * Hkv) * sizeof(double));
+    double *cv = ck + B * Hkv;
+    /* scores against the anchors as they stand */
+    for (int64_t b = 0; b < B; ++b) {
+        for (int64_t h = 0; h < Hkv; ++h) {
+            for (int which = 0; which < 2; ++which) {
+                const float *x = (which ? v : k) + (b * Hkv + h) * d;
+                const double *a = (which ? anchor_v : anchor_k) + (b * Hkv + h) * d;
+                double dot = 0.0, na = 0.0, nx = 0.0;
+                for (int64_t c = 0; c < d; ++c) {
+                    double ac = a[c];
+                    if (anchor_kind == 0)
+                        ac = seen[b] > 0 ? ac / (double)seen[b] : 0.0;
+                    dot += ac * (double)x[c];
+                    na += ac * ac;
+                    nx += (double)x[c] * (double)x[c];
+                }
+                double den = sqrt(na) * sqrt(nx);
+                if (den < TFO_EPS_COS)
+                    den = TFO_EPS_COS;
+                double cs = dot / den;
+                cs = cs > 1.0 ? 1.0 : (cs < -1.0 ? -1.0 : cs);
+                (which ? cv : ck)[b * Hkv + h] = cs;
+            }
+        }
+    }
+    tfo_fuse(ck, cv, B, Hkv, 1, fusion, fused, NULL);
+    free(ck);
+    /* decisions first, so that a full cache is found before any state changes */
+    float *new_tau = (float *)malloc((size_t)B * sizeof(float));
+    for (int64_t b = 0; b < B; ++b) {
+        float inv_t = seen[b] == 0 ? 0.0f : 1.0f / (float)seen[b];
+        float p_current = (float)skipped[b] * inv_t;
+        float diff = p_current - target;
+        new_tau[b] = fmaf(eta, diff, tau[b]);
+        float s = decide_on ? decide_on[b] : (float)fused[b];
+        skip[b] = (uint8_t)((seen[b] >= W) && (s > new_tau[b]));
+        if (!skip[b] && cache_len[b] >= capacity) {
+            free(new_tau);
+            return -1;
+        }
+    }
+    for (int64_t b = 0; b < B; ++b) {
+        tau[b] = new_tau[b];
+        for (int64_t h = 0; h < Hkv; ++h) {
+            const float *xk = k + (b * Hkv + h) * d, *xv = v + (b * Hkv + h) * d;
+            double *ak = anchor_k + (b * Hkv + h) * d, *av = anchor_v + (b * Hkv + h) * d;
+            for (int64_t c = 0; c < d; ++c) {
+                if (anchor_kind == 0) {
+                    ak[c] += (double)xk[c];
+                    av[c] += (double)xv[c];
+                } else {
+                    ak[c] = gamma * ak[c] + (1.0 - gamma) * (double)xk[c];
+                    av[c] = gamma * av[c] + (1.0 - gamma) * (double)xv[c];
+                }
+            }
+            if (!skip[b]) {
+                memcpy(k_cache + ((b * Hkv + h) * capacity + cache_len[b]) * d, xk,
+                       (size_t)d * sizeof(float));
+                memcpy(v_cache + ((b * Hkv + h) * capacity + cache_len[b]) * d, xv,
+                       (size_t)d * sizeof(float));
+            }
+        }
+        seen[b] += 1;
+        if (skip[b])
+            skipped[b] += 1;
+        else
+            cache_len[b] += 1;
+    }
+    free(new_tau);
+    /* attention of the kept tokens over their row's cache */
+    for (int64_t b = 0; b < B; ++b) {
+        for (int64_t hq = 0; hq < Hq; ++hq) {
+            double *out = o + (b * Hq + hq) * d;
+            for (int64_t c = 0; c < d; ++c)
+                out[c] = 0.0;
+            if (skip[b])
+                continue;
+            int64_t hk = hq / (Hq / Hkv), len = cache_len[b];
+            const float *qr = q + (b * Hq + hq) * d;
+            const float *Kc = k_cache + (b * Hkv + hk) * capacity * d;
+            const float *Vc = v_cache + (b * Hkv + hk) * capacity * d;
+            double *logit = (double *)malloc((size_t)len * sizeof(double));
+            double mx = -INFINITY, z = 0.0;
+            for (int64_t j = 0; j < len; ++j) {
+                double acc = 0.0;
+                for (int64_t c = 0; c < d; ++c)
+                    acc += (double)qr[c] * (double)Kc[j * d + c];
+                logit[j] = acc * scale;
+                if (logit[j] > mx)
+                    mx = logit[j];
+            }
+            for (int64_t j = 0; j < len; ++j) {
+                logit[j] = exp(logit[j] - mx);
+                z += logit[j];
+            }
+            for (int64_t j = 0; j < len; ++j)
+                for (int64_t c = 0; c < d; ++c)
+                    out[c] += logit[j] / z * (double)Vc[j * d + c];
+            free(logit);
+        }
+    }
+    return 0;
 }

@@ -459,3 +459,95 @@ def test_whole_path_on_first_workload():
         first[t] = i not in seen
         seen.add(i)
     assert S[~first][10:].mean() > S[first][1:].mean()
+
+
+# ------------------------------------------------------------------ per-token (decoding) form
+
+def _run_decode(q, k, v, **kw):
+    B, Hq, n, d = q.shape
+    st = oracle.DecodeState(B, Hq, k.shape[1], d, kw.pop("capacity", n), **kw)
+    F, S, O = [], [], []
+    for t in range(n):
+        o, s, f = st.step(q[:, :, t], k[:, :, t], v[:, :, t])
+        F.append(f), S.append(s), O.append(o)
+    return st, np.stack(F, 1), np.stack(S, 1), np.stack(O, 2)
+
+
+def test_decode_step_hand_worked_three_tokens():
+    # one head, d = 2, K = V: the scores are plain cosines with the mean of the rows before
+    # (one head: both variances are zero, alpha = 1/2, S = (s_k + s_v) / 2 = the cosine).
+    # Fixed threshold 0.5 (eta = 0), warm-up 1: token 0 kept; token 1 repeats token 0 (S = 1):
+    # skipped, zero output, not cached; token 2 is orthogonal to the mean (S = 0): kept, and it
+    # sees a cache of tokens 0 and 2 only.
+    x = np.array([[1, 0], [1, 0], [0, 1]], dtype=np.float32).reshape(1, 1, 3, 2)
+    L = 3.0
+    q = np.array([[0, 0], [5, 5], [0, L]], dtype=np.float32).reshape(1, 1, 3, 2)
+    st, F, S, O = _run_decode(q, x, x, target=0.5, eta=0.0, tau0=0.5, warmup=1)
+    np.testing.assert_allclose(F[0], [0, 1, 0], atol=1e-15)
+    assert list(S[0]) == [0, 1, 0]
+    assert st.seen[0] == 3 and st.skipped[0] == 1 and st.cache_len[0] == 2 and st.tau[0] == np.float32(0.5)
+    np.testing.assert_array_equal(st.k_cache[0, 0, :2], [[1, 0], [0, 1]])
+    np.testing.assert_allclose(st.anchor_k[0, 0], [2, 1])           # sums of ALL rows seen
+    np.testing.assert_allclose(O[0, 0, 0], [1, 0], atol=1e-15)      # alone in the cache
+    np.testing.assert_array_equal(O[0, 0, 1], [0, 0])
+    w2 = math.exp(L / math.sqrt(2)) / (1 + math.exp(L / math.sqrt(2)))
+    np.testing.assert_allclose(O[0, 0, 2], [1 - w2, w2], rtol=1e-14)
+
+
+@pytest.mark.parametrize("gamma,mode,hq,hkv", [(None, oracle.FUSE_EQ2, 4, 4), (0.9, oracle.FUSE_INVVAR, 6, 2),
+                                               (None, oracle.FUSE_KEY_ONLY, 2, 1), (0.5, oracle.FUSE_EQ2, 8, 4)])
+def test_decode_steps_reduce_to_the_batched_path(gamma, mode, hq, hkv):
+    # token by token = the batched definitions on the whole sequence: anchor cosines + fusion,
+    # the online decision on those scores, attention among the kept tokens
+    rng = np.random.default_rng(31)
+    B, n, d = 3, 90, 16
+    proto = rng.normal(size=(5, d))
+    z = rng.integers(0, 5, size=(B, 1, n))
+    k = (proto[z] + 0.4 * rng.normal(size=(B, hkv, n, d))).astype(np.float32)
+    v = (proto[z][..., ::-1] + 0.4 * rng.normal(size=(B, hkv, n, d))).astype(np.float32)
+    q = rng.normal(size=(B, hq, n, d)).astype(np.float32)
+    W, target, eta, tau0 = 3, 0.4, 0.05, 0.2
+    st, F, S, O = _run_decode(q, k, v, target=target, eta=eta, tau0=tau0, warmup=W, mode=mode,
+                              ema_gamma=gamma, scale=0.3)
+    cos = (lambda x: oracle.anchor_cosine(x)) if gamma is None else (lambda x: oracle.anchor_cosine_ema(x, gamma))
+    fb = oracle.fuse(cos(k), cos(v), mode)
+    np.testing.assert_allclose(F, fb, rtol=1e-12, atol=1e-14)
+    keep, idx, cnt, tau = oracle.select_online(fb, target, eta, tau0, W)
+    np.testing.assert_array_equal(S, 1 - keep)
+    assert 0 < (keep == 0).sum() < keep.size                 # both branches taken
+    np.testing.assert_array_equal(st.cache_len, cnt)
+    np.testing.assert_array_equal(st.seen, n)
+    np.testing.assert_array_equal(st.skipped, n - cnt)
+    np.testing.assert_array_equal(st.tau, tau)
+    for b in range(B):
+        np.testing.assert_array_equal(st.k_cache[b, :, :cnt[b]], k[b][:, idx[b, :cnt[b]]])
+        np.testing.assert_array_equal(st.v_cache[b, :, :cnt[b]], v[b][:, idx[b, :cnt[b]]])
+    rows = np.array([(b, h, i) for b in range(B) for h in range(hq) for i in range(cnt[b])], dtype=np.int32)
+    ref = oracle.attend_rows(q, k, v, idx, rows, scale=0.3)
+    got = np.stack([O[b, h, idx[b, i]] for b, h, i in rows])
+    np.testing.assert_allclose(got, ref, rtol=1e-12, atol=1e-14)
+    assert np.all(O[np.broadcast_to((keep == 0)[:, None, :, None], O.shape)] == 0)
+
+
+def test_decode_step_forced_decisions_and_full_cache():
+    rng = np.random.default_rng(32)
+    B, H, d = 2, 2, 8
+    st = oracle.DecodeState(B, H, H, d, 2, target=0.5, eta=0.0, tau0=0.0, warmup=0)
+    x = lambda: rng.normal(size=(B, H, d)).astype(np.float32)
+    # the decision follows the scores handed in, not the ones computed: row 0 kept, row 1 skipped
+    o, skip, fused = st.step(x(), x(), x(), decide_on=np.array([-1.0, 1.0], dtype=np.float32))
+    assert list(skip) == [0, 1] and list(st.cache_len) == [1, 0] and np.all(o[1] == 0) and np.any(o[0] != 0)
+    st.step(x(), x(), x(), decide_on=np.array([-1.0, 1.0], dtype=np.float32))
+    before = (st.anchor_k.copy(), st.seen.copy(), st.tau.copy(), st.cache_len.copy(), st.k_cache.copy())
+    with pytest.raises(OverflowError):                       # row 0's cache holds 2 rows already
+        st.step(x(), x(), x(), decide_on=np.array([-1.0, 1.0], dtype=np.float32))
+    for a, b in zip(before, (st.anchor_k, st.seen, st.tau, st.cache_len, st.k_cache)):
+        np.testing.assert_array_equal(a, b)
+    # a skipped token leaves no trace in what later tokens attend to: the output of a kept
+    # token is the softmax average of the cached values only
+    st2 = oracle.DecodeState(1, 1, 1, 2, 4, target=0.5, eta=0.0, tau0=0.0, warmup=0, scale=1.0)
+    one = lambda a, b: np.array([[[a, b]]], dtype=np.float32)
+    st2.step(one(0, 0), one(1, 0), one(10, 0), decide_on=np.array([-1.0], dtype=np.float32))
+    st2.step(one(0, 0), one(0, 9), one(0, 99), decide_on=np.array([1.0], dtype=np.float32))
+    o, _, _ = st2.step(one(0, 0), one(0, 1), one(0, 20), decide_on=np.array([-1.0], dtype=np.float32))
+    np.testing.assert_allclose(o[0, 0], [5, 10], rtol=1e-14)   # zero query: uniform over 2 rows
