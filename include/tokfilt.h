@@ -185,6 +185,56 @@ tf_status tf_filtered_attention(tf_ctx *ctx, const tf_params *p, const void *Q, 
                                 const void *V, uint8_t *keep, int32_t *kept_idx, float *fused,
                                 float *tau, void *O, void *ws, size_t ws_bytes, void *stream);
 
+/* Per-token form of the layer: Algorithm 1 called once per new token of every batch row
+ * (anchor of Section 3.2 / Eq. 1, fusion of Eq. 2, warm-up of Section 3.2, threshold rule of
+ * Section 3.3 / Eq. 4 exactly as in tf_select_online, zero output for a skipped token).
+ * The state lives in caller-owned DEVICE memory described by this host struct:
+ *   anchor_k, anchor_v  [batch][n_kv_heads][128] double.  TF_ANCHOR_MEAN: the sums of all keys /
+ *                       values seen so far (the mean is formed when a token is scored);
+ *                       TF_ANCHOR_EMA: the incremental anchors.  Every token is absorbed, kept or
+ *                       skipped.
+ *   seen, skipped       [batch] int32: tokens seen / skipped so far
+ *   tau                 [batch] float: the threshold
+ *   cache_len           [batch] int32: kept tokens in the row's cache
+ *   overflow            [batch] int32: set to 1 when a kept token did not fit the cache; that
+ *                       token is then handled as a skipped one (zero output, counted as skipped)
+ *   k_cache, v_cache    [batch][n_kv_heads][capacity][128] of p->dtype, 16-byte aligned: keys and
+ *                       values of the kept tokens in arrival order (a skipped token is neither
+ *                       cached nor attended to)
+ * p->seq and the strides of `p` are not used by the two calls below (they must still be valid);
+ * p->prune_ratio is the target skip ratio, p->warmup the number of tokens never skipped. */
+typedef struct {
+    double *anchor_k, *anchor_v;
+    int32_t *seen, *skipped;
+    float *tau;
+    int32_t *cache_len, *overflow;
+    void *k_cache, *v_cache;
+    int32_t capacity; /* rows per (batch, head) in the caches, >= 1 */
+    int32_t reserved; /* must be 0 */
+} tf_decode_state;
+
+/* Bytes of workspace tf_decode_step needs for `p` (0 if p is invalid). */
+size_t tf_decode_workspace_bytes(const tf_params *p);
+
+/* Start a sequence: anchors, counters, cache lengths and overflow flags to zero, tau to tau0. */
+tf_status tf_decode_init(tf_ctx *ctx, const tf_params *p, const tf_decode_state *state, float tau0,
+                         void *stream);
+
+/* One new token per batch row.  In this order: the token's key and value are scored against the
+ * anchors as they stand; tau <- fmaf(eta, (float)skipped * (1.0f / (float)seen) - target, tau)
+ * (P_current = 0 before the first token); the token is skipped iff seen >= p->warmup and
+ * fused > tau; the anchors absorb the token; a kept token is appended to the caches and its
+ * queries attend over the row's whole cache, itself included.  Run over a sequence from
+ * tf_decode_init this equals tf_filtered_attention_online on that sequence (scores to rounding;
+ * decisions equal whenever the scores compare equally with the thresholds).
+ *   q       in  [batch][n_q_heads][128], k, v  in [batch][n_kv_heads][128], contiguous, p->dtype
+ *   o       out [batch][n_q_heads][128]: attention output, all zero for a skipped token
+ *   skip    out [batch] u8: 1 = skipped
+ *   fused   out [batch] float: the score S_KV the decision was taken on */
+tf_status tf_decode_step(tf_ctx *ctx, const tf_params *p, float eta, const tf_decode_state *state,
+                         const void *q, const void *k, const void *v, void *o, uint8_t *skip,
+                         float *fused, void *ws, size_t ws_bytes, void *stream);
+
 /* Tail-focused layer schedule (Section 3.3, Eq. 3), host side: to meet the global budget
  * p_global in [0, 1], the last ceil(tail_fraction * n_layers) layers (0 < tail_fraction <= 1)
  * are pruned at p_global / tail_fraction (not above 1), the others at 0.

@@ -27,7 +27,8 @@ EXPORTS = ("tf_create", "tf_destroy", "tf_status_string", "tf_last_error", "tf_k
            "tf_workspace_bytes", "tf_score", "tf_select", "tf_attend", "tf_filtered_attention",
            "tf_stage_timing_enable", "tf_stage_timing_read", "tf_probe_hbm_read",
            "tf_probe_mfma_bf16", "tf_tail_schedule", "tf_filtered_attention_layers",
-           "tf_select_online", "tf_attend_ragged", "tf_filtered_attention_online")
+           "tf_select_online", "tf_attend_ragged", "tf_filtered_attention_online",
+           "tf_decode_workspace_bytes", "tf_decode_init", "tf_decode_step")
 
 
 class tf_params(ctypes.Structure):
@@ -39,6 +40,14 @@ class tf_params(ctypes.Structure):
                 ("warmup", ctypes.c_int32), ("fusion", ctypes.c_int32),
                 ("softmax_scale", ctypes.c_float), ("anchor", ctypes.c_int32),
                 ("ema_gamma", ctypes.c_float), ("reserved", ctypes.c_int32)]
+
+
+class tf_decode_state(ctypes.Structure):
+    _fields_ = [("anchor_k", ctypes.c_void_p), ("anchor_v", ctypes.c_void_p),
+                ("seen", ctypes.c_void_p), ("skipped", ctypes.c_void_p), ("tau", ctypes.c_void_p),
+                ("cache_len", ctypes.c_void_p), ("overflow", ctypes.c_void_p),
+                ("k_cache", ctypes.c_void_p), ("v_cache", ctypes.c_void_p),
+                ("capacity", ctypes.c_int32), ("reserved", ctypes.c_int32)]
 
 
 class TokfiltError(RuntimeError):
@@ -90,6 +99,13 @@ def lib():
         L.tf_tail_schedule.restype = ctypes.c_int
         L.tf_filtered_attention_layers.argtypes = [vp, pp, i32, dp] + [vpp] * 8 + [vp, sz, vp]
         L.tf_filtered_attention_layers.restype = ctypes.c_int
+        sp = ctypes.POINTER(tf_decode_state)
+        L.tf_decode_workspace_bytes.argtypes = [pp]
+        L.tf_decode_workspace_bytes.restype = sz
+        L.tf_decode_init.argtypes = [vp, pp, sp, flt, vp]
+        L.tf_decode_init.restype = ctypes.c_int
+        L.tf_decode_step.argtypes = [vp, pp, flt, sp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.tf_decode_step.restype = ctypes.c_int
         L.tf_probe_hbm_read.argtypes = [vp, vp, sz, vp, vp, ctypes.POINTER(ctypes.c_double)]
         L.tf_probe_mfma_bf16.argtypes = [vp, i32, vp, vp, ctypes.POINTER(ctypes.c_double)]
         for name in ("tf_score", "tf_select", "tf_attend", "tf_filtered_attention",
@@ -156,8 +172,49 @@ def tf_workspace_bytes(p: tf_params) -> int:
     return int(lib().tf_workspace_bytes(ctypes.byref(p)))
 
 
+def tf_decode_workspace_bytes(p: tf_params) -> int:
+    return int(lib().tf_decode_workspace_bytes(ctypes.byref(p)))
+
+
+class DecodeBuffers:
+    """Device memory of one decoding sequence: the state tf_decode_state describes, the
+    per-step outputs and the workspace (allocated through torch; nothing is computed here)."""
+
+    def __init__(self, p: tf_params, capacity: int, device="cuda:0"):
+        B, Hq, Hkv, d = p.batch, p.n_q_heads, p.n_kv_heads, p.head_dim
+        dt = torch.float32 if p.dtype == TF_F32 else torch.bfloat16
+        i32 = dict(dtype=torch.int32, device=device)
+        self.anchor_k = torch.empty((B, Hkv, d), dtype=torch.float64, device=device)
+        self.anchor_v = torch.empty((B, Hkv, d), dtype=torch.float64, device=device)
+        self.seen, self.skipped = torch.empty(B, **i32), torch.empty(B, **i32)
+        self.cache_len, self.overflow = torch.empty(B, **i32), torch.empty(B, **i32)
+        self.tau = torch.empty(B, dtype=torch.float32, device=device)
+        self.k_cache = torch.empty((B, Hkv, capacity, d), dtype=dt, device=device)
+        self.v_cache = torch.empty((B, Hkv, capacity, d), dtype=dt, device=device)
+        self.o = torch.empty((B, Hq, d), dtype=dt, device=device)
+        self.skip = torch.empty(B, dtype=torch.uint8, device=device)
+        self.fused = torch.empty(B, dtype=torch.float32, device=device)
+        self.ws = torch.empty((tf_decode_workspace_bytes(p),), dtype=torch.uint8, device=device)
+        st = tf_decode_state()
+        for name in ("anchor_k", "anchor_v", "seen", "skipped", "tau", "cache_len", "overflow",
+                     "k_cache", "v_cache"):
+            setattr(st, name, getattr(self, name).data_ptr())
+        st.capacity, st.reserved = int(capacity), 0
+        self.state = st
+
+
 class Context:
     """Owns a tf_ctx.  Methods mirror the C entry points one to one."""
+
+    def tf_decode_init(self, p, state, tau0, stream=None):
+        self._check(lib().tf_decode_init(self._h, ctypes.byref(p), ctypes.byref(state),
+                                         float(tau0), _stream(stream)))
+
+    def tf_decode_step(self, p, eta, state, q, k, v, o, skip, fused, ws, stream=None):
+        self._check(lib().tf_decode_step(
+            self._h, ctypes.byref(p), float(eta), ctypes.byref(state), _ptr(q), _ptr(k), _ptr(v),
+            _ptr(o), _ptr(skip), _ptr(fused), _ptr(ws),
+            0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
 
     def __init__(self, device: int = 0):
         self._h = ctypes.c_void_p()

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtokfilt.so")
 SOURCES = ("tokfilt_api.hip", "score_scan.hip", "fuse_select.hip", "attend_f32.hip", "attend_bf16.hip",
-           "probes.hip")
+           "decode.hip", "probes.hip")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed fp32 VALU forms are kept out of the generated code

@@ -1,0 +1,344 @@
+// Per-token form of the layer (Algorithm 1 called once per new token): score the new key and
+// value against the caller-held anchors, move the threshold, decide, absorb the token into the
+// anchors, append a kept token to the cache of kept keys / values and attend over that cache.
+// Three launches per step: decode_score_kernel (one workgroup per batch row), the split
+// attention over the cache, and the merge of the splits.
+#include <algorithm>
+
+#include "tf_kernels.h"
+
+namespace tf {
+
+namespace {
+
+constexpr double kEpsCos = 1e-8;
+constexpr double kEpsVar = 1e-12;
+constexpr float kLowest = -1e30f;  // "no key yet": finite, so differences of two of them are 0
+constexpr int kPartStride = kDecodePartFloats;  // partial result: 128 numerators, running max, sum
+
+// eight consecutive elements of a row as floats
+__device__ __forceinline__ void load8(const uint16_t* p, float* x)
+{
+    const uint4 r = *reinterpret_cast<const uint4*>(p);
+    const unsigned w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x[2 * i] = __uint_as_float(w[i] << 16);
+        x[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+    }
+}
+__device__ __forceinline__ void load8(const float* p, float* x)
+{
+    const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+    x[0] = a.x; x[1] = a.y; x[2] = a.z; x[3] = a.w;
+    x[4] = b.x; x[5] = b.y; x[6] = b.z; x[7] = b.w;
+}
+__device__ __forceinline__ void copy8(uint16_t* dst, const uint16_t* src)
+{
+    *reinterpret_cast<uint4*>(dst) = *reinterpret_cast<const uint4*>(src);
+}
+__device__ __forceinline__ void copy8(float* dst, const float* src)
+{
+    reinterpret_cast<float4*>(dst)[0] = reinterpret_cast<const float4*>(src)[0];
+    reinterpret_cast<float4*>(dst)[1] = reinterpret_cast<const float4*>(src)[1];
+}
+__device__ __forceinline__ void store_out(uint16_t* p, float v)
+{
+    const unsigned u = __float_as_uint(v);
+    *p = (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);  // round to nearest even
+}
+__device__ __forceinline__ void store_out(float* p, float v) { *p = v; }
+
+__device__ __forceinline__ double group16_sum(double v)
+{
+    v += __shfl_xor(v, 1);
+    v += __shfl_xor(v, 2);
+    v += __shfl_xor(v, 4);
+    v += __shfl_xor(v, 8);
+    return v;
+}
+
+__global__ void decode_init_kernel(double* anchor_k, double* anchor_v, long long n_anchor,
+                                   int32_t* seen, int32_t* skipped, float* tau, int32_t* cache_len,
+                                   int32_t* overflow, int B, float tau0)
+{
+    const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n_anchor) { anchor_k[i] = 0.0; anchor_v[i] = 0.0; }
+    if (i < B) { seen[i] = 0; skipped[i] = 0; tau[i] = tau0; cache_len[i] = 0; overflow[i] = 0; }
+}
+
+// One workgroup per batch row; a 16-lane group per (tensor, KV head) pair, eight columns a lane.
+// The float operations of the threshold rule are the ones of the batched online decision, in
+// the same order, with contraction switched off, so both forms agree bit for bit.
+#pragma clang fp contract(off)
+template <typename T>
+__global__ __launch_bounds__(1024) void decode_score_kernel(
+    const T* __restrict__ k, const T* __restrict__ v, double* __restrict__ anchor_k,
+    double* __restrict__ anchor_v, int32_t* __restrict__ seen, int32_t* __restrict__ skipped,
+    float* __restrict__ tau, int32_t* __restrict__ cache_len, int32_t* __restrict__ overflow,
+    T* __restrict__ k_cache, T* __restrict__ v_cache, int capacity, int Hkv, int ema, double gamma,
+    int fusion, int warmup, float target, float eta, uint8_t* __restrict__ skip_out,
+    float* __restrict__ fused_out)
+{
+    __shared__ double cosb[2][128];
+    __shared__ int slot_s;
+    const int b = blockIdx.x;
+    const int grp = threadIdx.x >> 4, c8 = threadIdx.x & 15, n_grp = blockDim.x >> 4;
+    const int t = seen[b];
+    const double inv_t = (!ema && t > 0) ? 1.0 / (double)t : (ema ? 1.0 : 0.0);
+
+    for (int pr = grp; pr < 2 * Hkv; pr += n_grp) {
+        const int w = pr >= Hkv, h = pr - w * Hkv;
+        const long long off = ((long long)b * Hkv + h) * kHeadDim + c8 * 8;
+        float x[8];
+        load8((w ? v : k) + off, x);
+        const double* a = (w ? anchor_v : anchor_k) + off;
+        double dot = 0.0, na = 0.0, nx = 0.0;
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const double ac = a[c] * inv_t;  // the mean (the anchor itself for the incremental kind)
+            dot += ac * (double)x[c];
+            na += ac * ac;
+            nx += (double)x[c] * (double)x[c];
+        }
+        dot = group16_sum(dot); na = group16_sum(na); nx = group16_sum(nx);
+        double den = sqrt(na) * sqrt(nx);
+        den = den < kEpsCos ? kEpsCos : den;
+        double cs = dot / den;
+        cs = cs > 1.0 ? 1.0 : (cs < -1.0 ? -1.0 : cs);
+        if (c8 == 0) cosb[w][h] = cs;
+    }
+    __syncthreads();  // every read of seen[b] above precedes thread 0's update below
+
+    if (threadIdx.x == 0) {
+        double sk = 0.0, sv = 0.0;
+        for (int h = 0; h < Hkv; ++h) { sk += cosb[0][h]; sv += cosb[1][h]; }
+        sk /= (double)Hkv; sv /= (double)Hkv;
+        double vk = 0.0, vv = 0.0;
+        for (int h = 0; h < Hkv; ++h) {
+            const double dk = cosb[0][h] - sk, dv = cosb[1][h] - sv;
+            vk += dk * dk; vv += dv * dv;
+        }
+        const double ek = vk / (double)Hkv + kEpsVar, ev = vv / (double)Hkv + kEpsVar;
+        const double alpha = fusion == 0 ? (1.0 / ev) / (1.0 / ek + 1.0 / ev)
+                           : fusion == 1 ? (1.0 / ek) / (1.0 / ek + 1.0 / ev)
+                           : fusion == 2 ? 1.0 : 0.0;
+        const float S = (float)(alpha * sk + (1.0 - alpha) * sv);
+
+        const int n_skipped = skipped[b];
+        const float inv = t == 0 ? 0.0f : 1.0f / (float)t;
+        const float p_current = (float)n_skipped * inv;
+        const float diff = p_current - target;
+        const float th = fmaf(eta, diff, tau[b]);
+        int skip = (t >= warmup) && (S > th);
+        int slot = -1;
+        if (!skip) {
+            slot = cache_len[b];
+            if (slot >= capacity) { overflow[b] = 1; skip = 1; slot = -1; }  // handled as skipped
+            else cache_len[b] = slot + 1;
+        }
+        tau[b] = th;
+        seen[b] = t + 1;
+        skipped[b] = n_skipped + skip;
+        skip_out[b] = (uint8_t)skip;
+        fused_out[b] = S;
+        slot_s = slot;
+    }
+    __syncthreads();
+    const int slot = slot_s;
+
+    for (int pr = grp; pr < 2 * Hkv; pr += n_grp) {
+        const int w = pr >= Hkv, h = pr - w * Hkv;
+        const long long off = ((long long)b * Hkv + h) * kHeadDim + c8 * 8;
+        const T* src = (w ? v : k) + off;
+        float x[8];
+        load8(src, x);
+        double* a = (w ? anchor_v : anchor_k) + off;
+#pragma unroll
+        for (int c = 0; c < 8; ++c)
+            a[c] = ema ? gamma * a[c] + (1.0 - gamma) * (double)x[c] : a[c] + (double)x[c];
+        if (slot >= 0)
+            copy8((w ? v_cache : k_cache) + (((long long)b * Hkv + h) * capacity + slot) * kHeadDim + c8 * 8, src);
+    }
+}
+#pragma clang fp contract(fast)
+
+// Attention of the new token over one slice of its row's cache, for the G query heads that
+// share a KV head.  A 16-lane group owns every 16th key of the slice and keeps its own running
+// (max, sum, numerators); groups are merged through shuffles and LDS, the slices by
+// decode_merge_kernel.  Partial result per (row, query head, slice): kPartStride floats.
+template <typename T, int G>
+__global__ __launch_bounds__(256) void decode_attend_kernel(
+    const T* __restrict__ q, const T* __restrict__ k_cache, const T* __restrict__ v_cache,
+    const int32_t* __restrict__ cache_len, const uint8_t* __restrict__ skip,
+    float* __restrict__ part, int Hq, int Hkv, int capacity, int n_split, float scale_log2e)
+{
+    __shared__ float merge[4][G][kPartStride];
+    const int sp = blockIdx.x % n_split;
+    const int hg = (blockIdx.x / n_split) % (Hq / G);  // group of G query heads
+    const int b = blockIdx.x / n_split / (Hq / G);
+    if (skip[b]) return;  // the merge kernel writes the zero row
+    const int hq0 = hg * G, hk = hq0 / (Hq / Hkv);
+    const int len = cache_len[b];
+    int chunk = (len + n_split - 1) / n_split;
+    chunk = (chunk + 15) & ~15;
+    const int lo = sp * chunk, hi = min(len, lo + chunk);
+    const int grp = threadIdx.x >> 4, c8 = threadIdx.x & 15, wave = threadIdx.x >> 6;
+
+    float qf[G][8], acc[G][8], mx[G], sum[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        load8(q + ((long long)b * Hq + hq0 + g) * kHeadDim + c8 * 8, qf[g]);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) { qf[g][c] *= scale_log2e; acc[g][c] = 0.f; }
+        mx[g] = kLowest; sum[g] = 0.f;
+    }
+    const long long row0 = ((long long)b * Hkv + hk) * capacity;
+    const T* kb = k_cache + row0 * kHeadDim + c8 * 8;
+    const T* vb = v_cache + row0 * kHeadDim + c8 * 8;
+
+    for (int j = lo + grp; j < hi; j += 64) {
+        float kk[4][8], vv[4][8];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int ju = min(j + 16 * u, hi - 1);  // a valid row; its score is discarded below
+            load8(kb + (long long)ju * kHeadDim, kk[u]);
+            load8(vb + (long long)ju * kHeadDim, vv[u]);
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            float s[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                float d = 0.f;
+#pragma unroll
+                for (int c = 0; c < 8; ++c) d = fmaf(qf[g][c], kk[u][c], d);
+                d = row16_sum(d);
+                s[u] = (j + 16 * u < hi) ? d : kLowest;
+            }
+            const float m_new = fmaxf(fmaxf(mx[g], fmaxf(s[0], s[1])), fmaxf(s[2], s[3]));
+            const float scale_old = exp2f(mx[g] - m_new);
+            float p[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) p[u] = exp2f(s[u] - m_new);
+            sum[g] = fmaf(sum[g], scale_old, (p[0] + p[1]) + (p[2] + p[3]));
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                float a = acc[g][c] * scale_old;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) a = fmaf(p[u], vv[u][c], a);
+                acc[g][c] = a;
+            }
+            mx[g] = m_new;
+        }
+    }
+
+    // merge the four groups of a wave (lanes 16 and 32 apart), then the four waves through LDS
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+#pragma unroll
+        for (int step = 16; step <= 32; step *= 2) {
+            const float m_o = __shfl_xor(mx[g], step);
+            const float m_new = fmaxf(mx[g], m_o);
+            const float w_me = exp2f(mx[g] - m_new), w_o = exp2f(m_o - m_new);
+            sum[g] = sum[g] * w_me + __shfl_xor(sum[g], step) * w_o;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) acc[g][c] = acc[g][c] * w_me + __shfl_xor(acc[g][c], step) * w_o;
+            mx[g] = m_new;
+        }
+        if ((threadIdx.x & 63) < 16) {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) merge[wave][g][c8 * 8 + c] = acc[g][c];
+            if (c8 == 0) { merge[wave][g][kHeadDim] = mx[g]; merge[wave][g][kHeadDim + 1] = sum[g]; }
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < G * kPartStride; i += blockDim.x) {
+        const int g = i / kPartStride, c = i - g * kPartStride;
+        float m_all = kLowest;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) m_all = fmaxf(m_all, merge[w][g][kHeadDim]);
+        float out;
+        if (c == kHeadDim) {
+            out = m_all;
+        } else {
+            out = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) out = fmaf(merge[w][g][c], exp2f(merge[w][g][kHeadDim] - m_all), out);
+        }
+        part[(((long long)b * Hq + hq0 + g) * n_split + sp) * kPartStride + c] = out;
+    }
+}
+
+// One workgroup of 128 threads per (row, query head): weighted sum of the slices' partial
+// results, or the zero row of a skipped token.
+template <typename T>
+__global__ __launch_bounds__(128) void decode_merge_kernel(const float* __restrict__ part,
+                                                           const uint8_t* __restrict__ skip,
+                                                           T* __restrict__ o, int Hq, int n_split)
+{
+    const int b = blockIdx.x / Hq;
+    const int c = threadIdx.x;
+    T* out = o + (long long)blockIdx.x * kHeadDim + c;
+    if (skip[b]) { store_out(out, 0.f); return; }
+    const float* pr = part + (long long)blockIdx.x * n_split * kPartStride;
+    float m_all = kLowest;
+    for (int s = 0; s < n_split; ++s) m_all = fmaxf(m_all, pr[s * kPartStride + kHeadDim]);
+    float num = 0.f, den = 0.f;
+    for (int s = 0; s < n_split; ++s) {
+        const float w = exp2f(pr[s * kPartStride + kHeadDim] - m_all);
+        num = fmaf(pr[s * kPartStride + c], w, num);
+        den = fmaf(pr[s * kPartStride + kHeadDim + 1], w, den);
+    }
+    store_out(out, num / den);
+}
+
+template <typename T>
+hipError_t launch_decode_step_t(const DecodeArgs& a, const T* q, const T* k, const T* v, T* o,
+                                hipStream_t s)
+{
+    const int threads = std::min(1024, (32 * a.Hkv + 63) / 64 * 64);  // 16 lanes per (tensor, head)
+    decode_score_kernel<T><<<dim3(a.B), dim3(threads), 0, s>>>(
+        k, v, a.anchor_k, a.anchor_v, a.seen, a.skipped, a.tau, a.cache_len, a.overflow,
+        (T*)a.k_cache, (T*)a.v_cache, a.capacity, a.Hkv, a.ema, a.gamma, a.fusion, a.warmup,
+        a.target, a.eta, a.skip, a.fused);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const int group = a.Hq / a.Hkv;
+    const float sl2 = a.scale * 1.4426950408889634f;
+#define TF_DECODE_ATTEND(G)                                                                       \
+    decode_attend_kernel<T, G><<<dim3(a.B * (a.Hq / G) * a.n_split), dim3(256), 0, s>>>(          \
+        q, (const T*)a.k_cache, (const T*)a.v_cache, a.cache_len, a.skip, a.part, a.Hq, a.Hkv,     \
+        a.capacity, a.n_split, sl2)
+    if (group == 8) TF_DECODE_ATTEND(8);
+    else if (group == 4) TF_DECODE_ATTEND(4);
+    else if (group == 2) TF_DECODE_ATTEND(2);
+    else TF_DECODE_ATTEND(1);  // other ratios: one query head per workgroup
+#undef TF_DECODE_ATTEND
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    decode_merge_kernel<T><<<dim3(a.B * a.Hq), dim3(128), 0, s>>>(a.part, a.skip, o, a.Hq, a.n_split);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_decode_init(const DecodeArgs& a, float tau0, hipStream_t s)
+{
+    const long long n_anchor = (long long)a.B * a.Hkv * kHeadDim;
+    const long long n = std::max<long long>(n_anchor, a.B);
+    decode_init_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(
+        a.anchor_k, a.anchor_v, n_anchor, a.seen, a.skipped, a.tau, a.cache_len, a.overflow, a.B, tau0);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_step(const DecodeArgs& a, int dtype, const void* q, const void* k,
+                              const void* v, void* o, hipStream_t s)
+{
+    if (dtype == 0)
+        return launch_decode_step_t<float>(a, (const float*)q, (const float*)k, (const float*)v, (float*)o, s);
+    return launch_decode_step_t<uint16_t>(a, (const uint16_t*)q, (const uint16_t*)k,
+                                          (const uint16_t*)v, (uint16_t*)o, s);
+}
+
+}  // namespace tf

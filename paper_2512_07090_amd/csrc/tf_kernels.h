@@ -70,6 +70,28 @@ hipError_t launch_attend_bf16(const Dims& d, float scale, const void* Q, const v
                               const void* V, const int32_t* kept_idx, void* O, int n_cu,
                               const int32_t* counts, long long idx_stride, hipStream_t s);
 
+// ---- per-token (decoding) form ----------------------------------------------------------------
+constexpr int kDecodeMaxSplit = 16;                 // slices of a row's cache per query head
+constexpr int kDecodePartFloats = kHeadDim + 2;     // floats of one slice's partial result
+struct DecodeArgs {
+    int B, Hq, Hkv, capacity;
+    double *anchor_k, *anchor_v;                    // [B][Hkv][128]
+    int32_t *seen, *skipped, *cache_len, *overflow; // [B]
+    float* tau;                                     // [B]
+    void *k_cache, *v_cache;                        // [B][Hkv][capacity][128]
+    int ema, fusion, warmup;
+    double gamma;
+    float target, eta, scale;
+    uint8_t* skip;                                  // out [B]
+    float* fused;                                   // out [B]
+    float* part;                                    // scratch [B][Hq][n_split][kDecodePartFloats]
+    int n_split;                                    // 1 .. kDecodeMaxSplit
+};
+hipError_t launch_decode_init(const DecodeArgs& a, float tau0, hipStream_t s);
+// q, o: [B][Hq][128]; k, v: [B][Hkv][128]
+hipError_t launch_decode_step(const DecodeArgs& a, int dtype, const void* q, const void* k,
+                              const void* v, void* o, hipStream_t s);
+
 // ---- measurement probes (not part of the path) ---------------------------------------------
 hipError_t launch_probe_stream_read(const void* src, size_t bytes, void* sink, int n_cu,
                                     hipStream_t s);

@@ -160,6 +160,35 @@ tf_status run_attend(tf_ctx* ctx, const tf_params* p, const tf::Dims& d, const v
                "bf16 attention launch");
 }
 
+// validation shared by the decode calls; fills everything of `a` the state and params determine
+tf_status decode_args(tf_ctx* ctx, const tf_params* p, const tf_decode_state* st, tf::DecodeArgs* a)
+{
+    const char* why;
+    const tf_status s = check_shape(p, &why);
+    if (s != TF_OK) return fail(ctx, s, "%s", why);
+    if (!st) return fail(ctx, TF_ERR_INVALID_ARG, "state is NULL");
+    if (!st->anchor_k || !st->anchor_v || !st->seen || !st->skipped || !st->tau || !st->cache_len ||
+        !st->overflow || !st->k_cache || !st->v_cache)
+        return fail(ctx, TF_ERR_INVALID_ARG, "a pointer of the decode state is NULL");
+    if (st->capacity < 1 || st->reserved != 0)
+        return fail(ctx, TF_ERR_INVALID_ARG, "decode state: capacity must be >= 1 and reserved 0");
+    if (misaligned(st->k_cache) || misaligned(st->v_cache) || misaligned(st->anchor_k) || misaligned(st->anchor_v))
+        return fail(ctx, TF_ERR_INVALID_ARG, "caches and anchors must be 16-byte aligned");
+    if ((int64_t)p->batch * p->n_kv_heads * (int64_t)st->capacity > ((int64_t)1 << 40) / tf::kHeadDim)
+        return fail(ctx, TF_ERR_UNSUPPORTED, "cache too large");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, TF_ERR_DEVICE, "hipSetDevice(%d) failed", ctx->device);
+    a->B = p->batch; a->Hq = p->n_q_heads; a->Hkv = p->n_kv_heads; a->capacity = st->capacity;
+    a->anchor_k = st->anchor_k; a->anchor_v = st->anchor_v;
+    a->seen = st->seen; a->skipped = st->skipped; a->cache_len = st->cache_len; a->overflow = st->overflow;
+    a->tau = st->tau; a->k_cache = st->k_cache; a->v_cache = st->v_cache;
+    a->ema = p->anchor == TF_ANCHOR_EMA; a->fusion = p->fusion; a->warmup = p->warmup;
+    a->gamma = (double)p->ema_gamma;
+    a->target = (float)p->prune_ratio; a->eta = 0.f;
+    a->scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
+    a->skip = nullptr; a->fused = nullptr; a->part = nullptr; a->n_split = 1;
+    return TF_OK;
+}
+
 }  // namespace
 
 namespace {
@@ -394,6 +423,56 @@ tf_status tf_filtered_attention_online(tf_ctx* ctx, const tf_params* p, float et
                                            kept_idx, count, tau, s), "online decision launch");
     if (st != TF_OK) return st;
     return run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, s, -1, count);
+}
+
+size_t tf_decode_workspace_bytes(const tf_params* p)
+{
+    const char* why;
+    if (check_shape(p, &why) != TF_OK) return 0;
+    return align256((size_t)p->batch * p->n_q_heads * tf::kDecodeMaxSplit * tf::kDecodePartFloats * sizeof(float));
+}
+
+tf_status tf_decode_init(tf_ctx* ctx, const tf_params* p, const tf_decode_state* state, float tau0,
+                         void* stream)
+{
+    if (!ctx) return TF_ERR_INVALID_ARG;
+    tf::DecodeArgs a;
+    tf_status st = decode_args(ctx, p, state, &a);
+    if (st != TF_OK) return st;
+    if (isnan(tau0) || isinf(tau0)) return fail(ctx, TF_ERR_INVALID_ARG, "tau0 must be finite");
+    return dev(ctx, tf::launch_decode_init(a, tau0, (hipStream_t)stream), "decode init launch");
+}
+
+tf_status tf_decode_step(tf_ctx* ctx, const tf_params* p, float eta, const tf_decode_state* state,
+                         const void* q, const void* k, const void* v, void* o, uint8_t* skip,
+                         float* fused, void* ws, size_t ws_bytes, void* stream)
+{
+    if (!ctx) return TF_ERR_INVALID_ARG;
+    tf::DecodeArgs a;
+    tf_status st = decode_args(ctx, p, state, &a);
+    if (st != TF_OK) return st;
+    if (!q || !k || !v || !o || !skip || !fused)
+        return fail(ctx, TF_ERR_INVALID_ARG, "q, k, v, o, skip and fused must not be NULL");
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(o))
+        return fail(ctx, TF_ERR_INVALID_ARG, "q, k, v and o must be 16-byte aligned");
+    if (!(eta >= 0.f) || isinf(eta)) return fail(ctx, TF_ERR_INVALID_ARG, "eta must be finite and >= 0");
+    if (!ws || misaligned(ws)) return fail(ctx, TF_ERR_INVALID_ARG, "workspace must be a 16-byte aligned pointer");
+    const size_t need = tf_decode_workspace_bytes(p);
+    if (ws_bytes < need)
+        return fail(ctx, TF_ERR_WORKSPACE_TOO_SMALL, "workspace has %zu bytes, %zu needed", ws_bytes, need);
+    a.eta = eta;
+    a.skip = skip;
+    a.fused = fused;
+    a.part = (float*)ws;
+    // enough workgroups for about four per compute unit, each slice at least one pass of keys
+    const int group = p->n_q_heads / p->n_kv_heads;
+    const int heads_per_wg = (group == 2 || group == 4 || group == 8) ? group : 1;
+    const int rows = p->batch * (p->n_q_heads / heads_per_wg);
+    int n_split = (4 * ctx->n_cu + rows - 1) / rows;
+    n_split = n_split < 1 ? 1 : (n_split > tf::kDecodeMaxSplit ? tf::kDecodeMaxSplit : n_split);
+    const int by_len = (state->capacity + 63) / 64;
+    a.n_split = n_split > by_len ? by_len : n_split;
+    return dev(ctx, tf::launch_decode_step(a, p->dtype, q, k, v, o, (hipStream_t)stream), "decode step launch");
 }
 
 tf_status tf_filtered_attention(tf_ctx* ctx, const tf_params* p, const void* Q, const void* K,

@@ -1,0 +1,218 @@
+"""Parity of the per-token (decoding) entry points with the CPU oracle, through the C ABI.
+
+The GPU runs a whole sequence token by token; the oracle then replays it step by step.  The
+oracle takes each decision on the GPU's score of that step (the threshold recurrence feeds its
+own decisions back, so a last-bit difference in a score that sits on the threshold would
+otherwise change everything after it); scores themselves are compared to the usual bound
+|gpu - oracle| <= 1e-5 |oracle| + 1e-6, decisions, counters, thresholds and cache contents bit
+for bit, attention outputs to 1e-4 (fp32) / 2e-2 (bf16).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2512_07090_amd import binding as B
+from paper_2512_07090_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+ATTN_TOL = {torch.float32: 1e-4, torch.bfloat16: 2e-2}
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    c = B.Context(0)
+    yield c
+    c.close()
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+def gpu_decode(ctx, q, k, v, target, eta, tau0, W, capacity, fusion=B.TF_FUSE_EQ2, scale=0.0,
+               ema_gamma=None, alloc_capacity=None):
+    """All n tokens through tf_decode_step.  Returns (buffers, O [n,B,Hq,d], skip [n,B], fused [n,B])."""
+    Bn, Hq, n, d = q.shape
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, target, W, fusion, scale,
+                      ema_gamma=ema_gamma)
+    buf = B.DecodeBuffers(p, alloc_capacity or capacity)
+    buf.state.capacity = capacity
+    buf.k_cache.fill_(-77.0)
+    buf.v_cache.fill_(-77.0)
+    qs = q.permute(2, 0, 1, 3).contiguous().cuda()        # [n][B][H][d]: one contiguous slice per step
+    ks = k.permute(2, 0, 1, 3).contiguous().cuda()
+    vs = v.permute(2, 0, 1, 3).contiguous().cuda()
+    O = torch.full((n, Bn, Hq, d), float("nan"), dtype=q.dtype, device="cuda:0")
+    skip = torch.full((n, Bn), 9, dtype=torch.uint8, device="cuda:0")
+    fused = torch.full((n, Bn), float("nan"), dtype=torch.float32, device="cuda:0")
+    ctx.tf_decode_init(p, buf.state, tau0)
+    for t in range(n):
+        ctx.tf_decode_step(p, eta, buf.state, qs[t], ks[t], vs[t], O[t], skip[t], fused[t], buf.ws)
+    torch.cuda.synchronize()
+    return buf, O.float().cpu().numpy().astype(np.float64), skip.cpu().numpy(), fused.cpu().numpy()
+
+
+def check_decode(ctx, q, k, v, target, eta, tau0, W, fusion=B.TF_FUSE_EQ2, scale=0.0,
+                 ema_gamma=None, capacity=None):
+    Bn, Hq, n, d = q.shape
+    Hkv = k.shape[1]
+    capacity = capacity or n
+    g32 = None if ema_gamma is None else float(np.float32(ema_gamma))   # the value the library sees
+    buf, O_g, skip_g, fused_g = gpu_decode(ctx, q, k, v, target, eta, tau0, W, capacity, fusion,
+                                           scale, ema_gamma)
+    assert not np.isnan(O_g).any() and not np.isnan(fused_g).any() and skip_g.max() <= 1
+    st = oracle.DecodeState(Bn, Hq, Hkv, d, capacity, target, eta, tau0, W, fusion, scale, g32)
+    qf, kf, vf = q.float().numpy(), k.float().numpy(), v.float().numpy()
+    worst = 0.0
+    for t in range(n):
+        o_r, skip_r, fused_r = st.step(qf[:, :, t], kf[:, :, t], vf[:, :, t], decide_on=fused_g[t])
+        assert np.all(np.abs(fused_g[t] - fused_r) <= 1e-5 * np.abs(fused_r) + 1e-6), "score, token %d" % t
+        np.testing.assert_array_equal(skip_g[t], skip_r, err_msg="decision, token %d" % t)
+        worst = max(worst, np.abs(O_g[t] - o_r).max())
+        assert np.all(O_g[t][skip_r == 1] == 0)
+    assert worst <= ATTN_TOL[q.dtype], "attention output, worst %.3e" % worst
+    for name in ("seen", "skipped", "cache_len", "tau"):
+        np.testing.assert_array_equal(getattr(buf, name).cpu().numpy(), getattr(st, name), err_msg=name)
+    assert np.all(buf.overflow.cpu().numpy() == 0)
+    kc, vc = buf.k_cache.float().cpu().numpy(), buf.v_cache.float().cpu().numpy()
+    for b in range(Bn):
+        c = int(st.cache_len[b])
+        np.testing.assert_array_equal(kc[b, :, :c], st.k_cache[b, :, :c])
+        np.testing.assert_array_equal(vc[b, :, :c], st.v_cache[b, :, :c])
+        assert np.all(kc[b, :, c:] == -77.0) and np.all(vc[b, :, c:] == -77.0)   # nothing past the end
+    np.testing.assert_allclose(buf.anchor_k.cpu().numpy(), st.anchor_k, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(buf.anchor_v.cpu().numpy(), st.anchor_v, rtol=1e-12, atol=1e-13)
+    return skip_g
+
+
+@pytest.mark.parametrize("case", [
+    # (dtype, B, Hq, Hkv, n, target, eta, tau0, W, fusion, gamma, scale)
+    ("f32", 2, 4, 4, 300, 0.5, 0.05, 0.5, 4, B.TF_FUSE_EQ2, None, 0.0),
+    ("bf16", 3, 8, 2, 700, 0.5, 0.02, 0.5, 8, B.TF_FUSE_INVVAR, 0.9, 0.0),
+    ("bf16", 2, 6, 2, 200, 0.3, 0.05, 0.4, 1, B.TF_FUSE_EQ2, None, 0.11),     # 3 query heads per KV head
+    ("bf16", 1, 8, 1, 150, 0.6, 0.1, 0.3, 0, B.TF_FUSE_KEY_ONLY, None, 0.0),  # 8 per KV head
+    ("f32", 1, 4, 2, 130, 0.5, 0.05, 0.5, 2, B.TF_FUSE_VALUE_ONLY, 0.5, 0.0),
+    ("bf16", 5, 2, 2, 40, 0.5, 0.0, 0.2, 3, B.TF_FUSE_EQ2, None, 0.0),        # fixed threshold, short
+])
+def test_decode_steps_match_oracle(ctx, case):
+    dt, Bn, Hq, Hkv, n, target, eta, tau0, W, fusion, gamma, scale = case
+    _say("decode %s" % (case,))
+    w = synth.scaled(synth.workload(0), batch=Bn, seq=n, n_q_heads=Hq, n_kv_heads=Hkv, dtype=dt)
+    q, k, v, _ = synth.make_qkv(w)
+    skip = check_decode(ctx, q, k, v, target, eta, tau0, W, fusion, scale, gamma)
+    if eta > 0:
+        assert 0 < skip.sum() < skip.size                 # both branches were exercised
+
+
+def test_decode_first_token_and_all_skipped_after_warmup(ctx):
+    """Token 0 has no anchor (score 0); a threshold far below every score skips everything after
+    the warm-up, so each row's cache holds exactly the warm-up tokens."""
+    _say("decode warm-up only")
+    q, k, v, _ = synth.make_random_qkv(2, 4, 4, 30, 128, dtype="bf16", seed=5)
+    buf, O_g, skip_g, fused_g = gpu_decode(ctx, q, k, v, 0.5, 0.0, -5.0, 3, capacity=30)
+    assert np.all(fused_g[0] == 0)
+    assert np.all(skip_g[:3] == 0) and np.all(skip_g[3:] == 1)
+    assert np.all(buf.cache_len.cpu().numpy() == 3) and np.all(buf.skipped.cpu().numpy() == 27)
+    assert np.all(O_g[3:] == 0)
+    # the first token attends to itself alone: its output is its value row
+    np.testing.assert_array_equal(O_g[0], v[:, :, 0].float().numpy().astype(np.float64))
+
+
+def test_decode_full_cache_sets_overflow_and_writes_nothing_past_it(ctx):
+    _say("decode overflow")
+    q, k, v, _ = synth.make_random_qkv(2, 2, 2, 12, 128, dtype="bf16", seed=6)
+    # nothing is ever skipped by the rule (threshold far above); the cache takes 5 tokens
+    buf, O_g, skip_g, fused_g = gpu_decode(ctx, q, k, v, 0.5, 0.0, 50.0, 1, capacity=5, alloc_capacity=9)
+    assert np.all(skip_g[:5] == 0) and np.all(skip_g[5:] == 1)
+    assert np.all(buf.overflow.cpu().numpy() == 1)
+    assert np.all(buf.cache_len.cpu().numpy() == 5) and np.all(buf.seen.cpu().numpy() == 12)
+    assert np.all(O_g[5:] == 0) and np.all(np.abs(O_g[:5]).max(axis=(1, 2, 3)) > 0)
+    # the tensors were allocated with 9 rows per head and declared with 5: with that declared
+    # row stride the first 2 * 2 * 5 rows may be written, nothing after them
+    kc = buf.k_cache.float().cpu().numpy().reshape(-1, 128)
+    assert np.all(kc[2 * 2 * 5:] == -77.0)
+
+
+def test_decode_argument_errors(ctx):
+    q, k, v, _ = synth.make_random_qkv(1, 2, 2, 4, 128, dtype="bf16", seed=7)
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.5)
+    buf = B.DecodeBuffers(p, 4)
+    ctx.tf_decode_init(p, buf.state, 0.5)
+    qd = q[:, :, 0].contiguous().cuda()
+    kd = k[:, :, 0].contiguous().cuda()
+    with pytest.raises(B.TokfiltError):                   # workspace too small
+        ctx.tf_decode_step(p, 0.1, buf.state, qd, kd, kd, buf.o, buf.skip, buf.fused, buf.ws[:16])
+    with pytest.raises(B.TokfiltError):                   # negative step size
+        ctx.tf_decode_step(p, -0.1, buf.state, qd, kd, kd, buf.o, buf.skip, buf.fused, buf.ws)
+    bad = B.tf_decode_state.from_buffer_copy(buf.state)
+    bad.capacity = 0
+    with pytest.raises(B.TokfiltError):
+        ctx.tf_decode_step(p, 0.1, bad, qd, kd, kd, buf.o, buf.skip, buf.fused, buf.ws)
+    bad = B.tf_decode_state.from_buffer_copy(buf.state)
+    bad.tau = None
+    with pytest.raises(B.TokfiltError):
+        ctx.tf_decode_init(p, bad, 0.5)
+    torch.cuda.synchronize()
+    assert np.all(buf.seen.cpu().numpy() == 0)            # nothing was enqueued by the failed calls
+
+
+def test_decode_agrees_with_batched_online_path(ctx):
+    """Token by token and all at once are the same computation: scores agree to the bound, and
+    where the two masks coincide the outputs agree to twice the attention tolerance."""
+    _say("decode vs batched online")
+    w = synth.scaled(synth.workload(1), batch=2, seq=900, n_q_heads=8, n_kv_heads=8)
+    q, k, v, _ = synth.make_qkv(w)
+    target, eta, tau0, W = 0.5, 0.02, 0.5, 8
+    buf, O_d, skip_d, fused_d = gpu_decode(ctx, q, k, v, target, eta, tau0, W, capacity=900)
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, target, W)
+    bb = B.Buffers(p, "cuda:0")
+    idx = torch.empty((2, 900), dtype=torch.int32, device="cuda:0")
+    cnt = torch.empty((2,), dtype=torch.int32, device="cuda:0")
+    ctx.tf_filtered_attention_online(p, eta, tau0, q.cuda(), k.cuda(), v.cuda(), bb.keep, idx, cnt,
+                                     bb.fused, bb.tau, bb.O, bb.ws)
+    torch.cuda.synchronize()
+    fused_b = bb.fused.cpu().numpy()
+    assert np.all(np.abs(fused_d.T - fused_b) <= 2e-5 * np.abs(fused_b) + 2e-6)
+    keep_b = bb.keep.cpu().numpy()
+    O_b = bb.O.float().cpu().numpy()
+    for b in range(2):
+        if np.array_equal(keep_b[b], 1 - skip_d[:, b]):
+            assert np.abs(O_d[:, b].transpose(1, 0, 2) - O_b[b]).max() <= 2 * ATTN_TOL[q.dtype]
+            assert buf.tau.cpu().numpy()[b] == bb.tau.cpu().numpy()[b]
+
+
+def test_decode_full_size_bench_shape(ctx):
+    """The benchmark's shape (8 rows, 32 heads, bf16, 4096 tokens): every decision against the
+    oracle's controller on the GPU's scores, the scores against the oracle's batched scoring,
+    and sampled output rows against the oracle's attention over the kept set."""
+    _say("decode full size")
+    w = synth.workload(1)
+    q, k, v, _ = synth.make_qkv(w)
+    Bn, Hq, n, d = q.shape
+    target, eta, tau0, W = 0.5, 0.02, 0.5, 8
+    buf, O_g, skip_g, fused_g = gpu_decode(ctx, q, k, v, target, eta, tau0, W, capacity=n)
+    ref = oracle.filtered_attention(q, k, v, target, W, with_attention=False)
+    assert np.all(np.abs(fused_g.T - ref["fused"]) <= 1e-5 * np.abs(ref["fused"]) + 1e-6)
+    keep_r, idx_r, cnt_r, tau_r = oracle.select_online(fused_g.T, target, eta, tau0, W)
+    np.testing.assert_array_equal(1 - skip_g.T, keep_r)
+    np.testing.assert_array_equal(buf.cache_len.cpu().numpy(), cnt_r)
+    np.testing.assert_array_equal(buf.tau.cpu().numpy(), tau_r)
+    assert np.all(buf.overflow.cpu().numpy() == 0)
+    assert np.all(O_g[skip_g == 1] == 0)
+    rng = np.random.default_rng(3)
+    rows = []
+    for b in range(Bn):
+        c = int(cnt_r[b])
+        for i in (0, 1, 63, 64, c // 2, c - 2, c - 1):
+            rows.append((b, int(rng.integers(Hq)), i))
+        rows += [(b, int(rng.integers(Hq)), int(rng.integers(c))) for _ in range(9)]
+    rows = np.array(rows, dtype=np.int32)
+    want = oracle.attend_rows(q, k, v, idx_r, rows)
+    got = np.stack([O_g[idx_r[b, i], b, h] for b, h, i in rows])
+    assert np.abs(got - want).max() <= ATTN_TOL[q.dtype]
+    # the cache of row 0, head 5 is the kept keys in order
+    c0 = int(cnt_r[0])
+    assert torch.equal(buf.k_cache[0, 5, :c0].cpu(), k[0, 5][torch.from_numpy(idx_r[0, :c0]).long()])
