@@ -242,6 +242,40 @@ def main():
                                        "kept_per_row": [int(x) for x in cnt4.cpu().tolist()]}
         del b4
 
+        # the per-token form: the workload's tokens one at a time (fills the anchors, the
+        # controller state and the cache of kept tokens), then K more steps timed; the
+        # attention of a step streams the row's cache once (HBM-bound)
+        p5 = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, args.ratio, warmup=8)
+        b5 = B.DecodeBuffers(p5, w.seq + K + args.warmup, dev)
+        qs = qd.permute(2, 0, 1, 3).contiguous()
+        ks = kd.permute(2, 0, 1, 3).contiguous()
+        vs = vd.permute(2, 0, 1, 3).contiguous()
+        ctx.tf_decode_init(p5, b5.state, 0.5)
+
+        def step5(t):
+            t %= w.seq
+            ctx.tf_decode_step(p5, 0.02, b5.state, qs[t], ks[t], vs[t], b5.o, b5.skip, b5.fused, b5.ws)
+        for t in range(w.seq + args.warmup):
+            step5(t)
+        len0 = b5.cache_len.sum().item()
+        torch.cuda.synchronize()
+        e0.record()
+        for t in range(K):
+            step5(w.seq + args.warmup + t)
+        e1.record()
+        torch.cuda.synchronize()
+        ms5 = e0.elapsed_time(e1) / K
+        len1 = b5.cache_len.sum().item()
+        kept5 = (len1 - len0) / (K * w.batch)               # fraction of the timed tokens that attended
+        esz = 2 if w.dtype == "bf16" else 4
+        cache_bytes = 0.5 * (len0 + len1) * kept5 * w.n_kv_heads * w.head_dim * 2 * esz
+        variants["decode_step"] = {"ms_per_step": round(ms5, 4),
+                                   "tokens_per_s": round(w.batch / (ms5 * 1e-3), 1),
+                                   "cache_rows_per_batch_row": round(0.5 * (len0 + len1) / w.batch, 1),
+                                   "kept_fraction": round(kept5, 3),
+                                   "cache_GBps": round(cache_bytes / (ms5 * 1e-3) / 1e9, 1)}
+        del b5, qs, ks, vs
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         import oracle

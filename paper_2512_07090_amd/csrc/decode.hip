@@ -70,7 +70,17 @@ __global__ void decode_init_kernel(double* anchor_k, double* anchor_v, long long
 // One workgroup per batch row; a 16-lane group per (tensor, KV head) pair, eight columns a lane.
 // The float operations of the threshold rule are the ones of the batched online decision, in
 // the same order, with contraction switched off, so both forms agree bit for bit.
+// Latency is what this kernel costs, so the row's scalars are fetched up front by the lane
+// that needs them, the head statistics are reduced by one wave rather than one lane, and the
+// first pair of a group stays in registers for the anchor update.
 #pragma clang fp contract(off)
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int s = 1; s < 64; s *= 2) v += __shfl_xor(v, s);
+    return v;
+}
+
 template <typename T>
 __global__ __launch_bounds__(1024) void decode_score_kernel(
     const T* __restrict__ k, const T* __restrict__ v, double* __restrict__ anchor_k,
@@ -85,18 +95,30 @@ __global__ __launch_bounds__(1024) void decode_score_kernel(
     const int b = blockIdx.x;
     const int grp = threadIdx.x >> 4, c8 = threadIdx.x & 15, n_grp = blockDim.x >> 4;
     const int t = seen[b];
-    const double inv_t = (!ema && t > 0) ? 1.0 / (double)t : (ema ? 1.0 : 0.0);
+    int n_skipped = 0, len = 0;
+    float th_old = 0.f;
+    if (threadIdx.x == 0) { n_skipped = skipped[b]; len = cache_len[b]; th_old = tau[b]; }
+    const double inv_t = ema ? 1.0 : (t > 0 ? 1.0 / (double)t : 0.0);
 
+    float x0[8];       // the group's first pair, kept for the update below
+    double a0[8];
     for (int pr = grp; pr < 2 * Hkv; pr += n_grp) {
         const int w = pr >= Hkv, h = pr - w * Hkv;
         const long long off = ((long long)b * Hkv + h) * kHeadDim + c8 * 8;
         float x[8];
         load8((w ? v : k) + off, x);
         const double* a = (w ? anchor_v : anchor_k) + off;
+        double av[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) av[c] = a[c];
+        if (pr == grp) {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) { x0[c] = x[c]; a0[c] = av[c]; }
+        }
         double dot = 0.0, na = 0.0, nx = 0.0;
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
-            const double ac = a[c] * inv_t;  // the mean (the anchor itself for the incremental kind)
+            const double ac = av[c] * inv_t;  // the mean (the anchor itself for the incremental kind)
             dot += ac * (double)x[c];
             na += ac * ac;
             nx += (double)x[c] * (double)x[c];
@@ -108,41 +130,41 @@ __global__ __launch_bounds__(1024) void decode_score_kernel(
         cs = cs > 1.0 ? 1.0 : (cs < -1.0 ? -1.0 : cs);
         if (c8 == 0) cosb[w][h] = cs;
     }
-    __syncthreads();  // every read of seen[b] above precedes thread 0's update below
+    __syncthreads();  // every read of seen[b] above precedes lane 0's update below
 
-    if (threadIdx.x == 0) {
-        double sk = 0.0, sv = 0.0;
-        for (int h = 0; h < Hkv; ++h) { sk += cosb[0][h]; sv += cosb[1][h]; }
-        sk /= (double)Hkv; sv /= (double)Hkv;
-        double vk = 0.0, vv = 0.0;
-        for (int h = 0; h < Hkv; ++h) {
-            const double dk = cosb[0][h] - sk, dv = cosb[1][h] - sv;
-            vk += dk * dk; vv += dv * dv;
-        }
-        const double ek = vk / (double)Hkv + kEpsVar, ev = vv / (double)Hkv + kEpsVar;
-        const double alpha = fusion == 0 ? (1.0 / ev) / (1.0 / ek + 1.0 / ev)
-                           : fusion == 1 ? (1.0 / ek) / (1.0 / ek + 1.0 / ev)
-                           : fusion == 2 ? 1.0 : 0.0;
-        const float S = (float)(alpha * sk + (1.0 - alpha) * sv);
+    if (threadIdx.x < 64) {
+        // mean and population variance over the heads (two passes), one wave
+        const int l = threadIdx.x;
+        const double ck0 = l < Hkv ? cosb[0][l] : 0.0, cv0 = l < Hkv ? cosb[1][l] : 0.0;
+        const double ck1 = l + 64 < Hkv ? cosb[0][l + 64] : 0.0, cv1 = l + 64 < Hkv ? cosb[1][l + 64] : 0.0;
+        const double sk = wave_sum(ck0 + ck1) / (double)Hkv, sv = wave_sum(cv0 + cv1) / (double)Hkv;
+        double dk = 0.0, dv = 0.0;
+        if (l < Hkv) { dk = (ck0 - sk) * (ck0 - sk); dv = (cv0 - sv) * (cv0 - sv); }
+        if (l + 64 < Hkv) { dk += (ck1 - sk) * (ck1 - sk); dv += (cv1 - sv) * (cv1 - sv); }
+        const double ek = wave_sum(dk) / (double)Hkv + kEpsVar, ev = wave_sum(dv) / (double)Hkv + kEpsVar;
+        if (l == 0) {
+            const double alpha = fusion == 0 ? (1.0 / ev) / (1.0 / ek + 1.0 / ev)
+                               : fusion == 1 ? (1.0 / ek) / (1.0 / ek + 1.0 / ev)
+                               : fusion == 2 ? 1.0 : 0.0;
+            const float S = (float)(alpha * sk + (1.0 - alpha) * sv);
 
-        const int n_skipped = skipped[b];
-        const float inv = t == 0 ? 0.0f : 1.0f / (float)t;
-        const float p_current = (float)n_skipped * inv;
-        const float diff = p_current - target;
-        const float th = fmaf(eta, diff, tau[b]);
-        int skip = (t >= warmup) && (S > th);
-        int slot = -1;
-        if (!skip) {
-            slot = cache_len[b];
-            if (slot >= capacity) { overflow[b] = 1; skip = 1; slot = -1; }  // handled as skipped
-            else cache_len[b] = slot + 1;
+            const float inv = t == 0 ? 0.0f : 1.0f / (float)t;
+            const float p_current = (float)n_skipped * inv;
+            const float diff = p_current - target;
+            const float th = fmaf(eta, diff, th_old);
+            int skip = (t >= warmup) && (S > th);
+            int slot = -1;
+            if (!skip) {
+                if (len >= capacity) { overflow[b] = 1; skip = 1; }  // handled as skipped
+                else { slot = len; cache_len[b] = len + 1; }
+            }
+            tau[b] = th;
+            seen[b] = t + 1;
+            skipped[b] = n_skipped + skip;
+            skip_out[b] = (uint8_t)skip;
+            fused_out[b] = S;
+            slot_s = slot;
         }
-        tau[b] = th;
-        seen[b] = t + 1;
-        skipped[b] = n_skipped + skip;
-        skip_out[b] = (uint8_t)skip;
-        fused_out[b] = S;
-        slot_s = slot;
     }
     __syncthreads();
     const int slot = slot_s;
@@ -151,12 +173,20 @@ __global__ __launch_bounds__(1024) void decode_score_kernel(
         const int w = pr >= Hkv, h = pr - w * Hkv;
         const long long off = ((long long)b * Hkv + h) * kHeadDim + c8 * 8;
         const T* src = (w ? v : k) + off;
-        float x[8];
-        load8(src, x);
         double* a = (w ? anchor_v : anchor_k) + off;
+        float x[8];
+        double av[8];
+        if (pr == grp) {
+#pragma unroll
+            for (int c = 0; c < 8; ++c) { x[c] = x0[c]; av[c] = a0[c]; }
+        } else {
+            load8(src, x);
+#pragma unroll
+            for (int c = 0; c < 8; ++c) av[c] = a[c];
+        }
 #pragma unroll
         for (int c = 0; c < 8; ++c)
-            a[c] = ema ? gamma * a[c] + (1.0 - gamma) * (double)x[c] : a[c] + (double)x[c];
+            a[c] = ema ? gamma * av[c] + (1.0 - gamma) * (double)x[c] : av[c] + (double)x[c];
         if (slot >= 0)
             copy8((w ? v_cache : k_cache) + (((long long)b * Hkv + h) * capacity + slot) * kHeadDim + c8 * 8, src);
     }
