@@ -149,18 +149,42 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
     const int n_pairs = (n_qt + 1) >> 1;
     const int n_entries = ng * n_pairs;
 
-    // Ragged rows (counts != null: every batch row has its own number of kept tokens, n_qt is
-    // the bound for the longest possible row): entries are listed pair-major, (pair p of group
-    // 0, pair p of group 1, ...), and an entry whose pair lies past the end of its row is empty.
+    // Ragged rows (counts != null: every batch row has its own number of kept tokens, read here
+    // on the device; n_qt is only the bound for the longest possible row): the XCD's list holds,
+    // group after group, as many pairs as the group's row needs (one entry for an empty row,
+    // which only has zero rows to write), so that, as in the uniform case, workgroups with
+    // neighbouring ids work on the same group.  (rb, row_e0): the batch row the current entry
+    // lies in and the first entry of that row; entries only move forward.
+    int rb = g_lo / d.Hq, row_e0 = 0;
     for (int it = 0;; ++it) {
     const int e = j + (it >> 1) * nwx;
-    if (e >= n_entries) break;
-    const int pr = counts ? e / ng : e % n_pairs;
-    const int bh = g_lo + (counts ? e % ng : e / n_pairs);
+    int pr, bh, m, nq;
+    if (counts) {
+        int P = 1;
+        bool done = false;
+        for (;;) {
+            const int lo = max(g_lo, rb * d.Hq), hi = min(g_lo + ng, (rb + 1) * d.Hq);
+            if (rb >= d.B || hi <= lo) { done = true; break; }
+            m = __builtin_amdgcn_readfirstlane(counts[rb]);  // kept tokens of this row
+            nq = (m + kBM - 1) / kBM;                        // its query tiles
+            P = m == 0 ? 1 : (nq + 1) >> 1;
+            if (e < row_e0 + (hi - lo) * P) break;
+            row_e0 += (hi - lo) * P;
+            ++rb;
+        }
+        if (done) break;
+        const int el = e - row_e0;
+        bh = max(g_lo, rb * d.Hq) + el / P;
+        pr = el % P;
+    } else {
+        if (e >= n_entries) break;
+        pr = e % n_pairs;
+        bh = g_lo + e / n_pairs;
+        m = d.m;
+        nq = n_qt;
+    }
     const int b = bh / d.Hq, hq = bh % d.Hq;
     const int hk = hq / (d.Hq / d.Hkv);
-    const int m = counts ? __builtin_amdgcn_readfirstlane(counts[b]) : d.m;  // kept tokens of this row
-    const int nq = counts ? (m + kBM - 1) / kBM : n_qt;                       // its query tiles
     if (m == 0) {
         // a row without kept tokens: nothing attends, every output row is zero
         if (pr == 0 && !(it & 1)) {
