@@ -220,6 +220,18 @@ size_t tf_decode_workspace_bytes(const tf_params *p);
 tf_status tf_decode_init(tf_ctx *ctx, const tf_params *p, const tf_decode_state *state, float tau0,
                          void *stream);
 
+/* Prompt, then decoding: tf_filtered_attention_online over a prompt of p->seq tokens (same
+ * arguments and outputs; the threshold after the last prompt token is written to state->tau),
+ * followed by the hand-off that leaves `state` exactly as p->seq calls of tf_decode_step from
+ * tf_decode_init(tau0) would have left it (anchors to rounding): anchors over all prompt rows,
+ * seen = seq, skipped = seq - count, cache_len = count, overflow = 0, and the kept rows of K and V
+ * copied to the caches in order.  state->capacity >= p->seq is required (the prompt may keep
+ * every token).  ws as for the batched calls (tf_workspace_bytes). */
+tf_status tf_decode_prefill(tf_ctx *ctx, const tf_params *p, float eta, float tau0,
+                            const tf_decode_state *state, const void *Q, const void *K,
+                            const void *V, uint8_t *keep, int32_t *kept_idx, int32_t *count,
+                            float *fused, void *O, void *ws, size_t ws_bytes, void *stream);
+
 /* One new token per batch row.  In this order: the token's key and value are scored against the
  * anchors as they stand; tau <- fmaf(eta, (float)skipped * (1.0f / (float)seen) - target, tau)
  * (P_current = 0 before the first token); the token is skipped iff seen >= p->warmup and

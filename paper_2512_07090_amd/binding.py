@@ -28,7 +28,7 @@ EXPORTS = ("tf_create", "tf_destroy", "tf_status_string", "tf_last_error", "tf_k
            "tf_stage_timing_enable", "tf_stage_timing_read", "tf_probe_hbm_read",
            "tf_probe_mfma_bf16", "tf_tail_schedule", "tf_filtered_attention_layers",
            "tf_select_online", "tf_attend_ragged", "tf_filtered_attention_online",
-           "tf_decode_workspace_bytes", "tf_decode_init", "tf_decode_step")
+           "tf_decode_workspace_bytes", "tf_decode_init", "tf_decode_step", "tf_decode_prefill")
 
 
 class tf_params(ctypes.Structure):
@@ -106,6 +106,8 @@ def lib():
         L.tf_decode_init.restype = ctypes.c_int
         L.tf_decode_step.argtypes = [vp, pp, flt, sp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.tf_decode_step.restype = ctypes.c_int
+        L.tf_decode_prefill.argtypes = [vp, pp, flt, flt, sp] + [vp] * 9 + [sz, vp]
+        L.tf_decode_prefill.restype = ctypes.c_int
         L.tf_probe_hbm_read.argtypes = [vp, vp, sz, vp, vp, ctypes.POINTER(ctypes.c_double)]
         L.tf_probe_mfma_bf16.argtypes = [vp, i32, vp, vp, ctypes.POINTER(ctypes.c_double)]
         for name in ("tf_score", "tf_select", "tf_attend", "tf_filtered_attention",
@@ -209,6 +211,13 @@ class Context:
     def tf_decode_init(self, p, state, tau0, stream=None):
         self._check(lib().tf_decode_init(self._h, ctypes.byref(p), ctypes.byref(state),
                                          float(tau0), _stream(stream)))
+
+    def tf_decode_prefill(self, p, eta, tau0, state, Q, K, V, keep, kept_idx, count, fused, O, ws,
+                          stream=None):
+        self._check(lib().tf_decode_prefill(
+            self._h, ctypes.byref(p), float(eta), float(tau0), ctypes.byref(state), _ptr(Q),
+            _ptr(K), _ptr(V), _ptr(keep), _ptr(kept_idx), _ptr(count), _ptr(fused), _ptr(O),
+            _ptr(ws), 0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
 
     def tf_decode_step(self, p, eta, state, q, k, v, o, skip, fused, ws, stream=None):
         self._check(lib().tf_decode_step(

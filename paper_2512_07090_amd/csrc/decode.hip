@@ -323,6 +323,95 @@ __global__ __launch_bounds__(128) void decode_merge_kernel(const float* __restri
     store_out(out, num / den);
 }
 
+// Hand-off from the batched path: the anchors as they stand after all n rows of a prompt.
+// One workgroup per (tensor, batch row, KV head); a 16-lane group folds every 16th row in
+// Horner form, A <- g^16 A + x (g = 1 for the exact mean, whose state is the plain sum), brings
+// its partial to the end of the prompt with g^(rows after its last one), and the 16 partials
+// are added through LDS.  All in double.  Rows further back than `window` from the end are
+// skipped (the incremental anchor forgets them: g^window is far below double resolution).
+template <typename T>
+__global__ __launch_bounds__(256) void decode_seed_anchor_kernel(
+    const T* __restrict__ K, const T* __restrict__ V, double* __restrict__ anchor_k,
+    double* __restrict__ anchor_v, int Hkv, int n, long long s_b, long long s_h, long long s_t,
+    double g, double weight, int window)
+{
+    __shared__ double part[16][kHeadDim];
+    const int w = blockIdx.x & 1, bh = blockIdx.x >> 1;
+    const int b = bh / Hkv, h = bh % Hkv;
+    const int grp = threadIdx.x >> 4, c8 = threadIdx.x & 15;
+    const T* X = (w ? V : K) + b * s_b + h * s_h + c8 * 8;
+    double g16 = g;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) g16 *= g16;
+    double a[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) a[c] = 0.0;
+    const int j0 = (n - window > 0 ? n - window : 0);
+    int last = -1;
+    for (int j = j0 + grp; j < n; j += 16) {
+        float x[8];
+        load8(X + (long long)j * s_t, x);
+#pragma unroll
+        for (int c = 0; c < 8; ++c) a[c] = g16 * a[c] + (double)x[c];
+        last = j;
+    }
+    double tail = weight;  // weight * g^(n - 1 - last)
+    for (int i = last; last >= 0 && i < n - 1; ++i) tail *= g;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) part[grp][c8 * 8 + c] = last >= 0 ? a[c] * tail : 0.0;
+    __syncthreads();
+    if (threadIdx.x < kHeadDim) {
+        double sum = 0.0;
+#pragma unroll
+        for (int q = 0; q < 16; ++q) sum += part[q][threadIdx.x];
+        (w ? anchor_v : anchor_k)[(long long)bh * kHeadDim + threadIdx.x] = sum;
+    }
+}
+
+// Hand-off from the batched path: the kept rows of K and V, in order, into the caches, and
+// the controller's counters.  Grid: (row blocks of 16, batch * KV heads).
+template <typename T>
+__global__ __launch_bounds__(256) void decode_seed_cache_kernel(
+    const T* __restrict__ K, const T* __restrict__ V, const int32_t* __restrict__ kept_idx,
+    const int32_t* __restrict__ count, T* __restrict__ k_cache, T* __restrict__ v_cache,
+    int32_t* __restrict__ seen, int32_t* __restrict__ skipped, int32_t* __restrict__ cache_len,
+    int32_t* __restrict__ overflow, int Hkv, int n, int capacity, long long s_b, long long s_h,
+    long long s_t)
+{
+    const int bh = blockIdx.y, b = bh / Hkv, h = bh % Hkv;
+    const int m = count[b];
+    if (blockIdx.x == 0 && h == 0 && threadIdx.x == 0) {
+        seen[b] = n; skipped[b] = n - m; cache_len[b] = m; overflow[b] = 0;
+    }
+    const int i = blockIdx.x * 16 + (threadIdx.x >> 4), c8 = threadIdx.x & 15;
+    if (i >= m) return;
+    const long long src = b * s_b + h * s_h + (long long)kept_idx[(long long)b * n + i] * s_t + c8 * 8;
+    const long long dst = ((long long)bh * capacity + i) * kHeadDim + c8 * 8;
+    copy8(k_cache + dst, K + src);
+    copy8(v_cache + dst, V + src);
+}
+
+template <typename T>
+hipError_t launch_decode_seed_t(const DecodeArgs& a, const T* K, const T* V, const int32_t* kept_idx,
+                                const int32_t* count, int n, const long long* kvs, hipStream_t s)
+{
+    const double g = a.ema ? a.gamma : 1.0;
+    // rows that still matter to the incremental anchor: g^window <= 1e-40
+    int window = n;
+    if (a.ema) {
+        const double rows = g > 0.0 ? ceil(-92.2 / log(g)) : 1.0;
+        window = rows < (double)n ? (int)rows : n;
+    }
+    decode_seed_anchor_kernel<T><<<dim3(2 * a.B * a.Hkv), dim3(256), 0, s>>>(
+        K, V, a.anchor_k, a.anchor_v, a.Hkv, n, kvs[0], kvs[1], kvs[2], g, a.ema ? 1.0 - a.gamma : 1.0, window);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    decode_seed_cache_kernel<T><<<dim3((n + 15) / 16, a.B * a.Hkv), dim3(256), 0, s>>>(
+        K, V, kept_idx, count, (T*)a.k_cache, (T*)a.v_cache, a.seen, a.skipped, a.cache_len, a.overflow,
+        a.Hkv, n, a.capacity, kvs[0], kvs[1], kvs[2]);
+    return hipGetLastError();
+}
+
 template <typename T>
 hipError_t launch_decode_step_t(const DecodeArgs& a, const T* q, const T* k, const T* v, T* o,
                                 hipStream_t s)
@@ -360,6 +449,14 @@ hipError_t launch_decode_init(const DecodeArgs& a, float tau0, hipStream_t s)
     decode_init_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s>>>(
         a.anchor_k, a.anchor_v, n_anchor, a.seen, a.skipped, a.tau, a.cache_len, a.overflow, a.B, tau0);
     return hipGetLastError();
+}
+
+hipError_t launch_decode_seed(const DecodeArgs& a, int dtype, const void* K, const void* V,
+                              const int32_t* kept_idx, const int32_t* count, int n,
+                              const long long* kvs, hipStream_t s)
+{
+    if (dtype == 0) return launch_decode_seed_t<float>(a, (const float*)K, (const float*)V, kept_idx, count, n, kvs, s);
+    return launch_decode_seed_t<uint16_t>(a, (const uint16_t*)K, (const uint16_t*)V, kept_idx, count, n, kvs, s);
 }
 
 hipError_t launch_decode_step(const DecodeArgs& a, int dtype, const void* q, const void* k,

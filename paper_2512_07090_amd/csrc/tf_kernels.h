@@ -88,6 +88,12 @@ struct DecodeArgs {
     int n_split;                                    // 1 .. kDecodeMaxSplit
 };
 hipError_t launch_decode_init(const DecodeArgs& a, float tau0, hipStream_t s);
+// state after a prompt of n rows that the batched online path has processed: anchors from K and
+// V (element strides kvs for batch, head, position), caches from the kept rows (kept_idx
+// [B][n], count [B]), counters; the threshold is written by the decision kernel itself
+hipError_t launch_decode_seed(const DecodeArgs& a, int dtype, const void* K, const void* V,
+                              const int32_t* kept_idx, const int32_t* count, int n,
+                              const long long* kvs, hipStream_t s);
 // q, o: [B][Hq][128]; k, v: [B][Hkv][128]
 hipError_t launch_decode_step(const DecodeArgs& a, int dtype, const void* q, const void* k,
                               const void* v, void* o, hipStream_t s);

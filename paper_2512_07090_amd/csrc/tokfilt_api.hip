@@ -443,6 +443,45 @@ tf_status tf_decode_init(tf_ctx* ctx, const tf_params* p, const tf_decode_state*
     return dev(ctx, tf::launch_decode_init(a, tau0, (hipStream_t)stream), "decode init launch");
 }
 
+tf_status tf_decode_prefill(tf_ctx* ctx, const tf_params* p, float eta, float tau0,
+                            const tf_decode_state* state, const void* Q, const void* K,
+                            const void* V, uint8_t* keep, int32_t* kept_idx, int32_t* count,
+                            float* fused, void* O, void* ws, size_t ws_bytes, void* stream)
+{
+    Workspace w;
+    tf_status st = enter(ctx, p, ws, ws_bytes, &w);
+    if (st != TF_OK) return st;
+    tf::DecodeArgs a;
+    st = decode_args(ctx, p, state, &a);
+    if (st != TF_OK) return st;
+    if (state->capacity < p->seq)
+        return fail(ctx, TF_ERR_INVALID_ARG, "the caches hold %d rows, the prompt may keep %d", state->capacity, p->seq);
+    if (!Q || !K || !V || !O || !keep || !kept_idx || !count || !fused)
+        return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V, O, keep, kept_idx, count and fused must not be NULL");
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O))
+        return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V and O must be 16-byte aligned");
+    if (!(eta >= 0.f) || isinf(eta) || isnan(tau0) || isinf(tau0))
+        return fail(ctx, TF_ERR_INVALID_ARG, "eta must be finite and >= 0, tau0 finite");
+    const tf::Dims d = make_dims(p, p->seq);
+    hipStream_t s = (hipStream_t)stream;
+    char* base = (char*)ws;
+    float* sk = (float*)(base + w.sim_k);
+    float* sv = (float*)(base + w.sim_v);
+    st = dev(ctx, tf::launch_score(d, p->dtype, K, V, sk, sv, (float*)(base + w.seg_tot),
+                                   score_tensors(p), p->anchor, p->ema_gamma, s), "score launch");
+    if (st != TF_OK) return st;
+    st = dev(ctx, tf::launch_fuse(d, p->fusion, sk, sv, fused, s), "fuse launch");
+    if (st != TF_OK) return st;
+    // the threshold after the last prompt token goes straight into the state
+    st = dev(ctx, tf::launch_select_online(d, p->warmup, (float)p->prune_ratio, eta, tau0, fused, keep,
+                                           kept_idx, count, state->tau, s), "online decision launch");
+    if (st != TF_OK) return st;
+    st = run_attend(ctx, p, d, Q, K, V, kept_idx, keep, O, s, -1, count);
+    if (st != TF_OK) return st;
+    return dev(ctx, tf::launch_decode_seed(a, p->dtype, K, V, kept_idx, count, p->seq, d.kvs, s),
+               "decode state hand-off launch");
+}
+
 tf_status tf_decode_step(tf_ctx* ctx, const tf_params* p, float eta, const tf_decode_state* state,
                          const void* q, const void* k, const void* v, void* o, uint8_t* skip,
                          float* fused, void* ws, size_t ws_bytes, void* stream)

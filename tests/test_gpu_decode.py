@@ -216,3 +216,94 @@ def test_decode_full_size_bench_shape(ctx):
     # the cache of row 0, head 5 is the kept keys in order
     c0 = int(cnt_r[0])
     assert torch.equal(buf.k_cache[0, 5, :c0].cpu(), k[0, 5][torch.from_numpy(idx_r[0, :c0]).long()])
+
+
+@pytest.mark.parametrize("case", [
+    # (dtype, B, Hq, Hkv, prompt, decoded, gamma, fusion)
+    ("bf16", 2, 8, 4, 600, 150, None, B.TF_FUSE_EQ2),
+    ("f32", 1, 4, 4, 300, 60, 0.9, B.TF_FUSE_INVVAR),
+    ("bf16", 3, 4, 2, 70, 30, 0.0, B.TF_FUSE_EQ2),          # gamma 0: the anchor is the previous row
+    ("bf16", 1, 2, 2, 1, 40, None, B.TF_FUSE_EQ2),          # a prompt of one token
+])
+def test_prefill_then_decode_matches_oracle(ctx, case):
+    """A prompt through the batched online path with the hand-off to the decoding state, then
+    single steps: the oracle goes through all tokens one by one."""
+    dt, Bn, Hq, Hkv, n1, n2, gamma, fusion = case
+    _say("prefill + decode %s" % (case,))
+    w = synth.scaled(synth.workload(0), batch=Bn, seq=n1 + n2, n_q_heads=Hq, n_kv_heads=Hkv, dtype=dt)
+    q, k, v, _ = synth.make_qkv(w)
+    target, eta, tau0, W = 0.5, 0.03, 0.5, 4
+    d = q.shape[3]
+    qp, kp, vp = (x[:, :, :n1].contiguous() for x in (q, k, v))
+    p = B.make_params(tuple(qp.shape), tuple(kp.shape), q.dtype, target, W, fusion, ema_gamma=gamma)
+    cap = n1 + n2
+    buf = B.DecodeBuffers(p, cap)
+    buf.k_cache.fill_(-77.0)
+    buf.v_cache.fill_(-77.0)
+    for t_ in (buf.seen, buf.skipped, buf.cache_len, buf.overflow):
+        t_.fill_(-5)
+    buf.anchor_k.fill_(float("nan"))
+    buf.anchor_v.fill_(float("nan"))
+    bb = B.Buffers(p, "cuda:0")
+    bb.O.fill_(float("nan"))
+    idx = torch.full((Bn, n1), -7, dtype=torch.int32, device="cuda:0")
+    cnt = torch.zeros((Bn,), dtype=torch.int32, device="cuda:0")
+    ctx.tf_decode_prefill(p, eta, tau0, buf.state, qp.cuda(), kp.cuda(), vp.cuda(), bb.keep, idx, cnt,
+                          bb.fused, bb.O, bb.ws)
+    torch.cuda.synchronize()
+    after_prefill = {name: getattr(buf, name).cpu().numpy().copy()
+                     for name in ("seen", "skipped", "cache_len", "tau", "overflow", "anchor_k", "anchor_v")}
+    qs = q[:, :, n1:].permute(2, 0, 1, 3).contiguous().cuda()
+    ks = k[:, :, n1:].permute(2, 0, 1, 3).contiguous().cuda()
+    vs = v[:, :, n1:].permute(2, 0, 1, 3).contiguous().cuda()
+    O2 = torch.full((n2, Bn, Hq, d), float("nan"), dtype=q.dtype, device="cuda:0")
+    skip2 = torch.full((n2, Bn), 9, dtype=torch.uint8, device="cuda:0")
+    fused2 = torch.full((n2, Bn), float("nan"), dtype=torch.float32, device="cuda:0")
+    for t in range(n2):
+        ctx.tf_decode_step(p, eta, buf.state, qs[t], ks[t], vs[t], O2[t], skip2[t], fused2[t], buf.ws)
+    torch.cuda.synchronize()
+
+    fused1 = bb.fused.cpu().numpy()
+    keep1 = bb.keep.cpu().numpy()
+    O1 = bb.O.float().cpu().numpy().astype(np.float64)
+    O2n, skip2n, fused2n = O2.float().cpu().numpy().astype(np.float64), skip2.cpu().numpy(), fused2.cpu().numpy()
+    g32 = None if gamma is None else float(np.float32(gamma))
+    st = oracle.DecodeState(Bn, Hq, Hkv, d, cap, target, eta, tau0, W, fusion, 0.0, g32)
+    qf, kf, vf = q.float().numpy(), k.float().numpy(), v.float().numpy()
+    tol = ATTN_TOL[q.dtype]
+    for t in range(n1 + n2):
+        gpu_fused = fused1[:, t] if t < n1 else fused2n[t - n1]
+        o_r, skip_r, fused_r = st.step(qf[:, :, t], kf[:, :, t], vf[:, :, t], decide_on=gpu_fused)
+        assert np.all(np.abs(gpu_fused - fused_r) <= 1e-5 * np.abs(fused_r) + 1e-6), "score, token %d" % t
+        if t < n1:
+            np.testing.assert_array_equal(1 - keep1[:, t], skip_r, err_msg="prompt decision, token %d" % t)
+            assert np.abs(O1[:, :, t] - o_r).max() <= tol, "prompt output, token %d" % t
+        else:
+            np.testing.assert_array_equal(skip2n[t - n1], skip_r, err_msg="decision, token %d" % t)
+            assert np.abs(O2n[t - n1] - o_r).max() <= tol, "output, token %d" % t
+        if t == n1 - 1:                                    # the state the hand-off must have produced
+            for name in ("seen", "skipped", "cache_len", "tau"):
+                np.testing.assert_array_equal(after_prefill[name], getattr(st, name), err_msg=name)
+            assert np.all(after_prefill["overflow"] == 0)
+            np.testing.assert_allclose(after_prefill["anchor_k"], st.anchor_k, rtol=1e-11, atol=1e-12)
+            np.testing.assert_allclose(after_prefill["anchor_v"], st.anchor_v, rtol=1e-11, atol=1e-12)
+    for name in ("seen", "skipped", "cache_len", "tau"):
+        np.testing.assert_array_equal(getattr(buf, name).cpu().numpy(), getattr(st, name), err_msg=name)
+    kc, vc = buf.k_cache.float().cpu().numpy(), buf.v_cache.float().cpu().numpy()
+    for b in range(Bn):
+        c = int(st.cache_len[b])
+        np.testing.assert_array_equal(kc[b, :, :c], st.k_cache[b, :, :c])
+        np.testing.assert_array_equal(vc[b, :, :c], st.v_cache[b, :, :c])
+        assert np.all(kc[b, :, c:] == -77.0) and np.all(vc[b, :, c:] == -77.0)
+
+
+def test_prefill_rejects_caches_shorter_than_the_prompt(ctx):
+    q, k, v, _ = synth.make_random_qkv(1, 2, 2, 64, 128, dtype="bf16", seed=8)
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.5)
+    buf = B.DecodeBuffers(p, 63)
+    bb = B.Buffers(p, "cuda:0")
+    idx = torch.empty((1, 64), dtype=torch.int32, device="cuda:0")
+    cnt = torch.empty((1,), dtype=torch.int32, device="cuda:0")
+    with pytest.raises(B.TokfiltError):
+        ctx.tf_decode_prefill(p, 0.02, 0.5, buf.state, q.cuda(), k.cuda(), v.cuda(), bb.keep, idx, cnt,
+                              bb.fused, bb.O, bb.ws)
