@@ -38,8 +38,8 @@ def _load():
         lib = ctypes.CDLL(build())
         i64, dbl, vp = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
         lib.tfo_num_threads.restype = ctypes.c_int
-        lib.tfo_anchor_cosine.argtypes = [vp, i64, i64, i64, i64, vp, vp]
-        lib.tfo_anchor_cosine_ema.argtypes = [vp, i64, i64, i64, i64, dbl, vp, vp]
+        lib.tfo_anchor_cosine.argtypes = [vp, i64, i64, i64, i64, ctypes.c_int, vp, vp]
+        lib.tfo_anchor_cosine_ema.argtypes = [vp, i64, i64, i64, i64, dbl, ctypes.c_int, vp, vp]
         lib.tfo_fuse.argtypes = [vp, vp, i64, i64, i64, ctypes.c_int, vp, vp]
         lib.tfo_keep_count.argtypes = [i64, dbl]
         lib.tfo_tail_schedule.argtypes = [i64, dbl, dbl, vp]
@@ -52,7 +52,7 @@ def _load():
         lib.tfo_attend_rows.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, vp, i64, dbl,
                                         vp, i64, vp]
         lib.tfo_decode_step.argtypes = [vp, vp, vp, i64, i64, i64, i64, ctypes.c_int, dbl,
-                                        ctypes.c_int, i64, flt, flt, dbl, vp, vp, vp, vp, vp, vp,
+                                        ctypes.c_int, ctypes.c_int, i64, flt, flt, dbl, vp, vp, vp, vp, vp, vp,
                                         vp, vp, vp, i64, vp, vp, vp]
         lib.tfo_decode_step.restype = ctypes.c_int
         _lib = lib
@@ -74,27 +74,29 @@ def _p(a: np.ndarray):
     return a.ctypes.data_as(ctypes.c_void_p)
 
 
-def anchor_cosine(x, return_anchors: bool = False):
-    """Per-head cosine of each token's row with the mean of the rows before it.
+def anchor_cosine(x, return_anchors: bool = False, inclusive: bool = False):
+    """Per-head cosine of each token's row with the mean of the rows before it (inclusive: of
+    the rows up to and including it).
     x: [B, H, n, d] -> cos [B, H, n] (float64); optionally the anchors [B, H, n, d]."""
     xa = _f32(x)
     B, H, n, d = xa.shape
     cosv = np.empty((B, H, n), dtype=np.float64)
     anchors = np.empty((B, H, n, d), dtype=np.float64) if return_anchors else None
-    _load().tfo_anchor_cosine(_p(xa), B, H, n, d, _p(cosv),
+    _load().tfo_anchor_cosine(_p(xa), B, H, n, d, int(inclusive), _p(cosv),
                               _p(anchors) if return_anchors else None)
     return (cosv, anchors) if return_anchors else cosv
 
 
-def anchor_cosine_ema(x, gamma: float, return_anchors: bool = False):
+def anchor_cosine_ema(x, gamma: float, return_anchors: bool = False, inclusive: bool = False):
     """Per-head cosine of each token's row with the incremental anchor of Eq. 1 as it stands
-    before that token (anchor <- gamma * anchor + (1 - gamma) * row, from zero).
+    before that token (anchor <- gamma * anchor + (1 - gamma) * row, from zero; inclusive: as
+    it stands after that token has been folded in).
     x: [B, H, n, d] -> cos [B, H, n] (float64); optionally the anchors [B, H, n, d]."""
     xa = _f32(x)
     B, H, n, d = xa.shape
     cosv = np.empty((B, H, n), dtype=np.float64)
     anchors = np.empty((B, H, n, d), dtype=np.float64) if return_anchors else None
-    _load().tfo_anchor_cosine_ema(_p(xa), B, H, n, d, float(gamma), _p(cosv),
+    _load().tfo_anchor_cosine_ema(_p(xa), B, H, n, d, float(gamma), int(inclusive), _p(cosv),
                                   _p(anchors) if return_anchors else None)
     return (cosv, anchors) if return_anchors else cosv
 
@@ -188,15 +190,17 @@ def attend_rows(q, k, v, kept_idx, rows, scale: float = 0.0):
 
 
 def filtered_attention(q, k, v, ratio: float, warmup: int = 1, mode: int = FUSE_EQ2,
-                       scale: float = 0.0, with_attention: bool = True, ema_gamma=None):
+                       scale: float = 0.0, with_attention: bool = True, ema_gamma=None,
+                       inclusive: bool = False):
     """The whole path: score -> fuse -> select -> attend.  Returns a dict of numpy arrays.
-    ema_gamma: None for the exact-mean anchor, else the smoothing factor of Eq. 1."""
+    ema_gamma: None for the exact-mean anchor, else the smoothing factor of Eq. 1.
+    inclusive: the anchor of a token includes that token."""
     if ema_gamma is None:
-        ck = anchor_cosine(k)
-        cv = anchor_cosine(v)
+        ck = anchor_cosine(k, inclusive=inclusive)
+        cv = anchor_cosine(v, inclusive=inclusive)
     else:
-        ck = anchor_cosine_ema(k, ema_gamma)
-        cv = anchor_cosine_ema(v, ema_gamma)
+        ck = anchor_cosine_ema(k, ema_gamma, inclusive=inclusive)
+        cv = anchor_cosine_ema(v, ema_gamma, inclusive=inclusive)
     S = fuse(ck, cv, mode)
     keep, idx, tau = select(S, ratio, warmup)
     out = {"sim_k": ck, "sim_v": cv, "fused": S, "keep": keep, "kept_idx": idx, "tau": tau}
@@ -212,11 +216,12 @@ class DecodeState:
 
     def __init__(self, batch: int, n_q_heads: int, n_kv_heads: int, head_dim: int, capacity: int,
                  target: float, eta: float, tau0: float, warmup: int = 1, mode: int = FUSE_EQ2,
-                 scale: float = 0.0, ema_gamma=None):
+                 scale: float = 0.0, ema_gamma=None, inclusive: bool = False):
         self.B, self.Hq, self.Hkv, self.d, self.capacity = batch, n_q_heads, n_kv_heads, head_dim, capacity
         self.target, self.eta, self.warmup, self.mode = float(target), float(eta), int(warmup), int(mode)
         self.scale = _scale(head_dim, scale)
         self.ema_gamma = ema_gamma
+        self.inclusive = bool(inclusive)
         self.anchor_k = np.zeros((batch, n_kv_heads, head_dim), dtype=np.float64)
         self.anchor_v = np.zeros((batch, n_kv_heads, head_dim), dtype=np.float64)
         self.seen = np.zeros(batch, dtype=np.int32)
@@ -239,7 +244,8 @@ class DecodeState:
         rc = _load().tfo_decode_step(
             _p(qa), _p(ka), _p(va), self.B, self.Hq, self.Hkv, self.d,
             0 if self.ema_gamma is None else 1,
-            0.0 if self.ema_gamma is None else float(self.ema_gamma), self.mode, self.warmup,
+            0.0 if self.ema_gamma is None else float(self.ema_gamma), int(self.inclusive),
+            self.mode, self.warmup,
             ctypes.c_float(self.target), ctypes.c_float(self.eta), self.scale,
             None if dec is None else _p(dec), _p(self.anchor_k), _p(self.anchor_v),
             _p(self.seen), _p(self.skipped), _p(self.tau), _p(self.cache_len), _p(self.k_cache),

@@ -19,6 +19,8 @@
  * Readings where the paper is silent or inconsistent (each is also listed in the design
  * document):
  *   - the anchor of token t excludes token t (prose: "previous"); token 0 has a zero anchor;
+ *     the other reading (Algorithm 1 forms the anchor from a K that already holds the current
+ *     token) is available as the flag `inclusive` of the anchor functions;
  *   - cosine denominator is max(|a| |x|, 1e-8) and the cosine is clamped to [-1, 1];
  *   - the variance is the population variance across heads for one token; 1e-12 is added to
  *     each variance before it is used in alpha;
@@ -61,12 +63,14 @@ int tfo_num_threads(void)
 }
 
 /* Incremental anchor (Section 3.2, Eq. 1): Anchor <- gamma * Anchor + (1 - gamma) * x_current,
- * one anchor per (b, h), starting from zero.  Row t is scored against the anchor as it stands
- * BEFORE row t is folded in (the reading "previous keys" of the exact mean, kept here), so
- * token 0 meets a zero anchor and scores 0 through the guard on the denominator.
+ * one anchor per (b, h), starting from zero.  inclusive = 0: row t is scored against the anchor
+ * as it stands BEFORE row t is folded in (the reading "previous keys" of the exact mean, kept
+ * here), so token 0 meets a zero anchor and scores 0 through the guard on the denominator.
+ * inclusive = 1: the anchor is updated first and row t is scored against the updated anchor
+ * (the order in which Algorithm 1 lists its steps).
  * cosv: [B][H][n].  anchors (optional, may be NULL): [B][H][n][d], the anchor each row met. */
 void tfo_anchor_cosine_ema(const float *X, int64_t B, int64_t H, int64_t n, int64_t d,
-                           double gamma, double *cosv, double *anchors)
+                           double gamma, int inclusive, double *cosv, double *anchors)
 {
 #pragma omp parallel for collapse(2) schedule(dynamic)
     for (int64_t b = 0; b < B; ++b) {
@@ -75,6 +79,9 @@ void tfo_anchor_cosine_ema(const float *X, int64_t B, int64_t H, int64_t n, int6
             const float *xbh = X + ((b * H + h) * n) * d;
             for (int64_t t = 0; t < n; ++t) {
                 const float *x = xbh + t * d;
+                if (inclusive)
+                    for (int64_t c = 0; c < d; ++c)
+                        anchor[c] = gamma * anchor[c] + (1.0 - gamma) * (double)x[c];
                 if (anchors)
                     memcpy(anchors + (((b * H + h) * n) + t) * d, anchor,
                            (size_t)d * sizeof(double));
@@ -94,8 +101,9 @@ void tfo_anchor_cosine_ema(const float *X, int64_t B, int64_t H, int64_t n, int6
                 if (cs < -1.0)
                     cs = -1.0;
                 cosv[(b * H + h) * n + t] = cs;
-                for (int64_t c = 0; c < d; ++c)
-                    anchor[c] = gamma * anchor[c] + (1.0 - gamma) * (double)x[c];
+                if (!inclusive)
+                    for (int64_t c = 0; c < d; ++c)
+                        anchor[c] = gamma * anchor[c] + (1.0 - gamma) * (double)x[c];
             }
             free(anchor);
         }
@@ -103,10 +111,12 @@ void tfo_anchor_cosine_ema(const float *X, int64_t B, int64_t H, int64_t n, int6
 }
 
 /* Anchor (Algorithm 1, anchor lines; Section 3.2): for each (b, h, t) the mean of rows
- * 0..t-1 of X[b][h], and the cosine similarity of that mean with row t.
+ * 0..t-1 of X[b][h] (inclusive = 1: of rows 0..t, the current row included, which is what
+ * Algorithm 1's mean over a K that ends with the current token says literally), and the cosine
+ * similarity of that mean with row t.
  * cosv: [B][H][n].  anchors (optional, may be NULL): [B][H][n][d], the means themselves. */
 void tfo_anchor_cosine(const float *X, int64_t B, int64_t H, int64_t n, int64_t d,
-                       double *cosv, double *anchors)
+                       int inclusive, double *cosv, double *anchors)
 {
 #pragma omp parallel for collapse(2) schedule(dynamic)
     for (int64_t b = 0; b < B; ++b) {
@@ -116,8 +126,12 @@ void tfo_anchor_cosine(const float *X, int64_t B, int64_t H, int64_t n, int64_t 
             const float *xbh = X + ((b * H + h) * n) * d;
             for (int64_t t = 0; t < n; ++t) {
                 const float *x = xbh + t * d;
+                if (inclusive)
+                    for (int64_t c = 0; c < d; ++c)
+                        sum[c] += (double)x[c];
+                int64_t rows = inclusive ? t + 1 : t;
                 for (int64_t c = 0; c < d; ++c)
-                    anchor[c] = (t == 0) ? 0.0 : sum[c] / (double)t;
+                    anchor[c] = (rows == 0) ? 0.0 : sum[c] / (double)rows;
                 if (anchors)
                     memcpy(anchors + (((b * H + h) * n) + t) * d, anchor,
                            (size_t)d * sizeof(double));
@@ -137,8 +151,9 @@ void tfo_anchor_cosine(const float *X, int64_t B, int64_t H, int64_t n, int64_t 
                 if (cs < -1.0)
                     cs = -1.0;
                 cosv[(b * H + h) * n + t] = cs;
-                for (int64_t c = 0; c < d; ++c)
-                    sum[c] += (double)x[c];
+                if (!inclusive)
+                    for (int64_t c = 0; c < d; ++c)
+                        sum[c] += (double)x[c];
             }
             free(sum);
             free(anchor);
@@ -399,8 +414,9 @@ void tfo_attend_rows(const float *Q, const float *K, const float *V, int64_t B, 
  *   seen, skipped: tokens seen / skipped so far;  tau: the threshold (float);
  *   cache_len: rows held in the cache;  k_cache, v_cache [B][Hkv][capacity][d]: keys / values of
  *       the kept tokens in arrival order.
- * Steps, in this order: the new key and value are scored against the anchors as they stand (the
- * anchors never include the current token, and they include every earlier token, kept or not);
+ * Steps, in this order: the new key and value are scored against the anchors as they stand (they
+ * include every earlier token, kept or not, and not the current one; with inclusive = 1 against
+ * the anchors as they will stand once the current token is absorbed);
  * the threshold moves exactly as in tfo_select_online (float arithmetic); the token is skipped
  * iff seen >= W and S > tau (S rounded to float); the anchors absorb the token; a kept token is
  * appended to the cache and attends over the whole cache, itself included (a skipped token is
@@ -410,7 +426,8 @@ void tfo_attend_rows(const float *Q, const float *K, const float *V, int64_t B, 
  * o: [B][Hq][d] double.  skip: [B] 0/1.  fused: [B] double.
  * Returns 0, or -1 if a kept token does not fit its row's cache (nothing is changed then). */
 int tfo_decode_step(const float *q, const float *k, const float *v, int64_t B, int64_t Hq,
-                    int64_t Hkv, int64_t d, int anchor_kind, double gamma, int fusion, int64_t W,
+                    int64_t Hkv, int64_t d, int anchor_kind, double gamma, int inclusive,
+                    int fusion, int64_t W,
                     float target, float eta, double scale, const float *decide_on,
                     double *anchor_k, double *anchor_v, int32_t *seen, int32_t *skipped,
                     float *tau, int32_t *cache_len, float *k_cache, float *v_cache,
@@ -427,8 +444,14 @@ int tfo_decode_step(const float *q, const float *k, const float *v, int64_t B, i
                 double dot = 0.0, na = 0.0, nx = 0.0;
                 for (int64_t c = 0; c < d; ++c) {
                     double ac = a[c];
-                    if (anchor_kind == 0)
-                        ac = seen[b] > 0 ? ac / (double)seen[b] : 0.0;
+                    if (anchor_kind == 0) {
+                        if (inclusive)
+                            ac = (ac + (double)x[c]) / (double)(seen[b] + 1);
+                        else
+                            ac = seen[b] > 0 ? ac / (double)seen[b] : 0.0;
+                    } else if (inclusive) {
+                        ac = gamma * ac + (1.0 - gamma) * (double)x[c];
+                    }
                     dot += ac * (double)x[c];
                     na += ac * ac;
                     nx += (double)x[c] * (double)x[c];

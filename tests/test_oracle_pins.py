@@ -551,3 +551,67 @@ def test_decode_step_forced_decisions_and_full_cache():
     st2.step(one(0, 0), one(0, 9), one(0, 99), decide_on=np.array([1.0], dtype=np.float32))
     o, _, _ = st2.step(one(0, 0), one(0, 1), one(0, 20), decide_on=np.array([-1.0], dtype=np.float32))
     np.testing.assert_allclose(o[0, 0], [5, 10], rtol=1e-14)   # zero query: uniform over 2 rows
+
+
+# ------------------------------------------------------------------ anchor that includes the token
+
+def test_inclusive_anchor_closed_forms_and_brute_force():
+    # x0 = (3, 4), x1 = (4, 3): the mean of both is (3.5, 3.5); cos with x1 = 24.5 / (sqrt(24.5) * 5)
+    x = np.array([[3.0, 4.0], [4.0, 3.0]], dtype=np.float32).reshape(1, 1, 2, 2)
+    c, a = oracle.anchor_cosine(x, return_anchors=True, inclusive=True)
+    np.testing.assert_array_equal(a[0, 0], [[3, 4], [3.5, 3.5]])
+    assert c[0, 0, 0] == 1.0                                   # a token against itself
+    assert abs(c[0, 0, 1] - math.sqrt(24.5) / 5) < 1e-15
+    # incremental anchor, gamma = 1/2, from zero: A0 = x0 / 2 (cos 1), A1 = x0 / 4 + x1 / 2 = (2.75, 2.5)
+    c, a = oracle.anchor_cosine_ema(x, 0.5, return_anchors=True, inclusive=True)
+    np.testing.assert_array_equal(a[0, 0], [[1.5, 2.0], [2.75, 2.5]])
+    assert abs(c[0, 0, 0] - 1.0) < 1e-15
+    assert abs(c[0, 0, 1] - 18.5 / (math.sqrt(2.75 ** 2 + 2.5 ** 2) * 5)) < 1e-15
+    # brute force on random rows, both kinds
+    rng = np.random.default_rng(41)
+    xr = rng.normal(size=(2, 3, 25, 6)).astype(np.float32)
+    xd = xr.astype(np.float64)
+    c, a = oracle.anchor_cosine(xr, return_anchors=True, inclusive=True)
+    ce, ae = oracle.anchor_cosine_ema(xr, 0.8, return_anchors=True, inclusive=True)
+    for t in range(25):
+        ref = xd[:, :, :t + 1].mean(axis=2)
+        np.testing.assert_allclose(a[:, :, t], ref, rtol=1e-13, atol=1e-15)
+        cs = (ref * xd[:, :, t]).sum(-1) / (np.linalg.norm(ref, axis=-1) * np.linalg.norm(xd[:, :, t], axis=-1))
+        np.testing.assert_allclose(c[:, :, t], cs, rtol=1e-12)
+        w = 0.2 * 0.8 ** (t - np.arange(t + 1))
+        refe = np.einsum("j,bhjd->bhd", w, xd[:, :, :t + 1])
+        np.testing.assert_allclose(ae[:, :, t], refe, rtol=1e-12, atol=1e-15)
+        cse = (refe * xd[:, :, t]).sum(-1) / (np.linalg.norm(refe, axis=-1) * np.linalg.norm(xd[:, :, t], axis=-1))
+        np.testing.assert_allclose(ce[:, :, t], cse, rtol=1e-12)
+    # the inclusive anchor of token t is the exclusive anchor of token t + 1
+    _, ax = oracle.anchor_cosine(xr, return_anchors=True)
+    np.testing.assert_allclose(a[:, :, :-1], ax[:, :, 1:], rtol=1e-14, atol=1e-16)
+    _, axe = oracle.anchor_cosine_ema(xr, 0.8, return_anchors=True)
+    np.testing.assert_allclose(ae[:, :, :-1], axe[:, :, 1:], rtol=1e-14, atol=1e-16)
+    # a zero row still scores 0 through the guard; including the token raises the score of a
+    # token that differs from its past
+    z = np.zeros((1, 1, 3, 4), dtype=np.float32)
+    z[0, 0, 0] = [1, 0, 0, 0]
+    assert oracle.anchor_cosine(z, inclusive=True)[0, 0, 1] == 0
+    assert np.all(c[:, :, 1:] > oracle.anchor_cosine(xr)[:, :, 1:])
+
+
+def test_inclusive_decode_steps_reduce_to_the_batched_scores():
+    rng = np.random.default_rng(42)
+    B, H, n, d = 2, 3, 40, 8
+    k = rng.normal(size=(B, H, n, d)).astype(np.float32) + 0.5
+    v = rng.normal(size=(B, H, n, d)).astype(np.float32) - 0.5
+    q = rng.normal(size=(B, H, n, d)).astype(np.float32)
+    for gamma in (None, 0.7):
+        st = oracle.DecodeState(B, H, H, d, n, 0.5, 0.05, 0.9, 2, ema_gamma=gamma, inclusive=True)
+        F = np.stack([st.step(q[:, :, t], k[:, :, t], v[:, :, t])[2] for t in range(n)], 1)
+        cos = (lambda x: oracle.anchor_cosine(x, inclusive=True)) if gamma is None else \
+              (lambda x: oracle.anchor_cosine_ema(x, gamma, inclusive=True))
+        np.testing.assert_allclose(F, oracle.fuse(cos(k), cos(v)), rtol=1e-12, atol=1e-14)
+        # the state itself does not depend on the flag
+        st0 = oracle.DecodeState(B, H, H, d, n, 0.5, 0.0, 9.0, 2, ema_gamma=gamma)
+        st1 = oracle.DecodeState(B, H, H, d, n, 0.5, 0.0, 9.0, 2, ema_gamma=gamma, inclusive=True)
+        for t in range(5):
+            st0.step(q[:, :, t], k[:, :, t], v[:, :, t])
+            st1.step(q[:, :, t], k[:, :, t], v[:, :, t])
+        np.testing.assert_array_equal(st0.anchor_k, st1.anchor_k)
