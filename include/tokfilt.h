@@ -87,7 +87,10 @@ typedef struct {
     int32_t anchor;        /* tf_anchor; 0 (the exact mean) is the default */
     float ema_gamma;       /* smoothing factor of TF_ANCHOR_EMA, 0 <= gamma < 1 (the paper
                               uses 0.9); ignored for TF_ANCHOR_MEAN */
-    int32_t reserved;      /* must be 0 */
+    int32_t anchor_inclusive; /* 0 (default): a token is compared with the anchor of the tokens
+                              before it (the prose's "previous keys"); 1: with the anchor that
+                              already includes the token itself (Algorithm 1 forms its anchor from
+                              a K whose last row is the current token) */
 } tf_params;
 
 /* Stages of the path, the order of tf_stage_timing_read's output. */

@@ -39,7 +39,7 @@ class tf_params(ctypes.Structure):
                 ("o_stride", ctypes.c_int64 * 3), ("prune_ratio", ctypes.c_double),
                 ("warmup", ctypes.c_int32), ("fusion", ctypes.c_int32),
                 ("softmax_scale", ctypes.c_float), ("anchor", ctypes.c_int32),
-                ("ema_gamma", ctypes.c_float), ("reserved", ctypes.c_int32)]
+                ("ema_gamma", ctypes.c_float), ("anchor_inclusive", ctypes.c_int32)]
 
 
 class tf_decode_state(ctypes.Structure):
@@ -130,10 +130,11 @@ def _stream(stream):
 
 def make_params(q_shape, kv_shape, dtype: torch.dtype, prune_ratio: float, warmup: int = 1,
                 fusion: int = TF_FUSE_EQ2, softmax_scale: float = 0.0, q_stride=None,
-                kv_stride=None, o_stride=None, ema_gamma=None) -> tf_params:
+                kv_stride=None, o_stride=None, ema_gamma=None,
+                anchor_inclusive: bool = False) -> tf_params:
     """tf_params for contiguous [B, H, n, d] tensors unless strides (in elements, for batch,
     head, position) are given.  ema_gamma: None for the exact-mean anchor, else the smoothing
-    factor of the incremental anchor."""
+    factor of the incremental anchor.  anchor_inclusive: a token's anchor includes the token."""
     B, Hq, n, d = q_shape
     Hkv = kv_shape[1]
     p = tf_params()
@@ -145,7 +146,7 @@ def make_params(q_shape, kv_shape, dtype: torch.dtype, prune_ratio: float, warmu
     for i in range(3):
         p.q_stride[i], p.kv_stride[i], p.o_stride[i] = qs[i], ks[i], os_[i]
     p.prune_ratio, p.warmup, p.fusion = float(prune_ratio), int(warmup), int(fusion)
-    p.softmax_scale, p.reserved = float(softmax_scale), 0
+    p.softmax_scale, p.anchor_inclusive = float(softmax_scale), int(bool(anchor_inclusive))
     p.anchor = TF_ANCHOR_MEAN if ema_gamma is None else TF_ANCHOR_EMA
     p.ema_gamma = 0.0 if ema_gamma is None else float(ema_gamma)
     return p

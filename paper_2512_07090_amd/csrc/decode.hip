@@ -87,8 +87,8 @@ __global__ __launch_bounds__(1024) void decode_score_kernel(
     double* __restrict__ anchor_v, int32_t* __restrict__ seen, int32_t* __restrict__ skipped,
     float* __restrict__ tau, int32_t* __restrict__ cache_len, int32_t* __restrict__ overflow,
     T* __restrict__ k_cache, T* __restrict__ v_cache, int capacity, int Hkv, int ema, double gamma,
-    int fusion, int warmup, float target, float eta, uint8_t* __restrict__ skip_out,
-    float* __restrict__ fused_out)
+    int inclusive, int fusion, int warmup, float target, float eta,
+    uint8_t* __restrict__ skip_out, float* __restrict__ fused_out)
 {
     __shared__ double cosb[2][128];
     __shared__ int slot_s;
@@ -98,7 +98,10 @@ __global__ __launch_bounds__(1024) void decode_score_kernel(
     int n_skipped = 0, len = 0;
     float th_old = 0.f;
     if (threadIdx.x == 0) { n_skipped = skipped[b]; len = cache_len[b]; th_old = tau[b]; }
-    const double inv_t = ema ? 1.0 : (t > 0 ? 1.0 / (double)t : 0.0);
+    // the anchor a row is compared with is f_a * state + f_x * row
+    const int rows_in = inclusive ? t + 1 : t;
+    const double f_a = ema ? (inclusive ? gamma : 1.0) : (rows_in > 0 ? 1.0 / (double)rows_in : 0.0);
+    const double f_x = inclusive ? (ema ? 1.0 - gamma : f_a) : 0.0;
 
     float x0[8];       // the group's first pair, kept for the update below
     double a0[8];
@@ -118,7 +121,7 @@ __global__ __launch_bounds__(1024) void decode_score_kernel(
         double dot = 0.0, na = 0.0, nx = 0.0;
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
-            const double ac = av[c] * inv_t;  // the mean (the anchor itself for the incremental kind)
+            const double ac = av[c] * f_a + (double)x[c] * f_x;
             dot += ac * (double)x[c];
             na += ac * ac;
             nx += (double)x[c] * (double)x[c];
@@ -419,7 +422,7 @@ hipError_t launch_decode_step_t(const DecodeArgs& a, const T* q, const T* k, con
     const int threads = std::min(1024, (32 * a.Hkv + 63) / 64 * 64);  // 16 lanes per (tensor, head)
     decode_score_kernel<T><<<dim3(a.B), dim3(threads), 0, s>>>(
         k, v, a.anchor_k, a.anchor_v, a.seen, a.skipped, a.tau, a.cache_len, a.overflow,
-        (T*)a.k_cache, (T*)a.v_cache, a.capacity, a.Hkv, a.ema, a.gamma, a.fusion, a.warmup,
+        (T*)a.k_cache, (T*)a.v_cache, a.capacity, a.Hkv, a.ema, a.gamma, a.inclusive, a.fusion, a.warmup,
         a.target, a.eta, a.skip, a.fused);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

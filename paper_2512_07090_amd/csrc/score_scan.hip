@@ -140,7 +140,7 @@ __global__ __launch_bounds__(kThreads) void segment_totals_kernel(
 // no weight left); no totals pass is needed.
 // first_tensor: 0 to walk K and V, or, with a single tensor (key-only / value-only scores),
 // the tensor to walk (0 = K, 1 = V).
-template <typename T, bool EMA>
+template <typename T, bool EMA, bool INCL>
 __global__ __launch_bounds__(kThreads) void scan_score_kernel(
     const T* __restrict__ K, const T* __restrict__ V, long long s_b, long long s_h, long long s_t,
     int BH, int Hkv, int n, int nseg, int seg_len, const float* __restrict__ seg_tot,
@@ -279,9 +279,24 @@ __global__ __launch_bounds__(kThreads) void scan_score_kernel(
                 // cosine of row t with the MEAN of rows 0..t-1: numerator and denominator
                 // both carry the 1/t so that the 1e-8 floor applies to |mean| * |x|
                 // (the incremental anchor is carried as it is and needs no factor)
-                const float inv_t = EMA ? 1.0f : (t > 0 ? 1.0f / (float)t : 0.f);
-                const float den = fmaxf(sqrtf(my_aa) * sqrtf(my_xx) * inv_t, 1e-8f);
-                float cs = (my_dot * inv_t) / den;
+                // (INCL: against the anchor with row t already absorbed, whose product with
+                // the row and whose norm follow from the same three reductions)
+                float num = my_dot, aa = my_aa;
+                int rows_in = t;
+                if (INCL) {
+                    if (EMA) {
+                        num = fmaf(g1, my_dot, w1 * my_xx);
+                        aa = fmaf(g2, my_aa, fmaf(2.f * g1 * w1, my_dot, w1 * w1 * my_xx));
+                    } else {
+                        num = my_dot + my_xx;
+                        aa = fmaf(2.f, my_dot, my_aa + my_xx);
+                        rows_in = t + 1;
+                    }
+                    aa = fmaxf(aa, 0.f);
+                }
+                const float inv_t = EMA ? 1.0f : (rows_in > 0 ? 1.0f / (float)rows_in : 0.f);
+                const float den = fmaxf(sqrtf(aa) * sqrtf(my_xx) * inv_t, 1e-8f);
+                float cs = (num * inv_t) / den;
                 cs = fminf(1.f, fmaxf(-1.f, cs));
                 sim[t] = cs;
             }
@@ -338,6 +353,8 @@ static hipError_t launch_score_t(const Dims& d, const T* K, const T* V, float* s
     const int n_tensors = tensors == 0 ? 2 : 1;
     const int first_tensor = tensors == 2 ? 1 : 0;
     const int chains = n_tensors * BH;
+    const int inclusive = anchor >> 1;  // bit 1 of `anchor`: the anchor of a row includes the row
+    anchor &= 1;
     if (anchor == 1) {
         // segments only if their warm-up is at most as long as they are
         const int warm = ema_warm_rows(gamma);
@@ -348,9 +365,14 @@ static hipError_t launch_score_t(const Dims& d, const T* K, const T* V, float* s
             const int tiles_per_seg = (tiles + nseg - 1) / nseg;
             p = ScorePlan{(tiles + tiles_per_seg - 1) / tiles_per_seg, tiles_per_seg * kTile};
         }
-        scan_score_kernel<T, true><<<dim3(chains * p.nseg), dim3(kThreads), 0, s>>>(
-            K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k,
-            sim_v, first_tensor, gamma, warm);
+        if (inclusive)
+            scan_score_kernel<T, true, true><<<dim3(chains * p.nseg), dim3(kThreads), 0, s>>>(
+                K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k,
+                sim_v, first_tensor, gamma, warm);
+        else
+            scan_score_kernel<T, true, false><<<dim3(chains * p.nseg), dim3(kThreads), 0, s>>>(
+                K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k,
+                sim_v, first_tensor, gamma, warm);
         return hipGetLastError();
     }
     if (p.nseg > 1) {
@@ -358,9 +380,14 @@ static hipError_t launch_score_t(const Dims& d, const T* K, const T* V, float* s
             K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot,
             first_tensor);
     }
-    scan_score_kernel<T, false><<<dim3(chains * p.nseg), dim3(kThreads), 0, s>>>(
-        K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k,
-        sim_v, first_tensor, 0.f, 0);
+    if (inclusive)
+        scan_score_kernel<T, false, true><<<dim3(chains * p.nseg), dim3(kThreads), 0, s>>>(
+            K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k,
+            sim_v, first_tensor, 0.f, 0);
+    else
+        scan_score_kernel<T, false, false><<<dim3(chains * p.nseg), dim3(kThreads), 0, s>>>(
+            K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k,
+            sim_v, first_tensor, 0.f, 0);
     return hipGetLastError();
 }
 

@@ -26,8 +26,8 @@ struct ScorePlan {
 ScorePlan plan_score(int B, int Hkv, int n);
 size_t score_scratch_floats(const Dims& d);  // segment totals
 // sim_k / sim_v: [B][Hkv][n] float.  seg_tot: scratch of score_scratch_floats() floats.
-// tensors: 0 = K and V, 1 = K only, 2 = V only.  anchor: 0 = exact mean, 1 = incremental
-// anchor with smoothing factor gamma.
+// tensors: 0 = K and V, 1 = K only, 2 = V only.  anchor: bit 0: 0 = exact mean, 1 = incremental
+// anchor with smoothing factor gamma; bit 1: the anchor of a row includes that row.
 hipError_t launch_score(const Dims& d, int dtype, const void* K, const void* V, float* sim_k,
                         float* sim_v, float* seg_tot, int tensors, int anchor, float gamma,
                         hipStream_t s);
@@ -79,7 +79,7 @@ struct DecodeArgs {
     int32_t *seen, *skipped, *cache_len, *overflow; // [B]
     float* tau;                                     // [B]
     void *k_cache, *v_cache;                        // [B][Hkv][capacity][128]
-    int ema, fusion, warmup;
+    int ema, inclusive, fusion, warmup;
     double gamma;
     float target, eta, scale;
     uint8_t* skip;                                  // out [B]

@@ -62,7 +62,7 @@ tf_status check_shape(const tf_params* p, const char** why)
         *why = "prune_ratio must be in [0, 1)"; return TF_ERR_INVALID_ARG;
     }
     if (p->warmup < 0) { *why = "warmup must be >= 0"; return TF_ERR_INVALID_ARG; }
-    if (p->reserved != 0) { *why = "reserved must be 0"; return TF_ERR_INVALID_ARG; }
+    if (p->anchor_inclusive != 0 && p->anchor_inclusive != 1) { *why = "anchor_inclusive must be 0 or 1"; return TF_ERR_INVALID_ARG; }
     if (p->anchor != TF_ANCHOR_MEAN && p->anchor != TF_ANCHOR_EMA) { *why = "unknown anchor"; return TF_ERR_INVALID_ARG; }
     if (p->anchor == TF_ANCHOR_EMA && !(p->ema_gamma >= 0.f && p->ema_gamma < 1.f)) {
         *why = "ema_gamma must be in [0, 1)"; return TF_ERR_INVALID_ARG;
@@ -88,6 +88,9 @@ int score_tensors(const tf_params* p)
 {
     return p->fusion == TF_FUSE_KEY_ONLY ? 1 : (p->fusion == TF_FUSE_VALUE_ONLY ? 2 : 0);
 }
+
+// anchor kind and the inclusive flag as the scoring launcher takes them
+int anchor_bits(const tf_params* p) { return p->anchor | (p->anchor_inclusive << 1); }
 
 tf::Dims make_dims(const tf_params* p, int m)
 {
@@ -181,7 +184,7 @@ tf_status decode_args(tf_ctx* ctx, const tf_params* p, const tf_decode_state* st
     a->anchor_k = st->anchor_k; a->anchor_v = st->anchor_v;
     a->seen = st->seen; a->skipped = st->skipped; a->cache_len = st->cache_len; a->overflow = st->overflow;
     a->tau = st->tau; a->k_cache = st->k_cache; a->v_cache = st->v_cache;
-    a->ema = p->anchor == TF_ANCHOR_EMA; a->fusion = p->fusion; a->warmup = p->warmup;
+    a->ema = p->anchor == TF_ANCHOR_EMA; a->inclusive = p->anchor_inclusive; a->fusion = p->fusion; a->warmup = p->warmup;
     a->gamma = (double)p->ema_gamma;
     a->target = (float)p->prune_ratio; a->eta = 0.f;
     a->scale = p->softmax_scale > 0.f ? p->softmax_scale : 1.0f / sqrtf((float)p->head_dim);
@@ -208,7 +211,7 @@ tf_status run_path(tf_ctx* ctx, const tf_params* p, const Workspace& w, const vo
 
     mark(ctx, slot, 0, s);
     tf_status st = dev(ctx, tf::launch_score(d, p->dtype, K, V, sk, sv, (float*)(base + w.seg_tot),
-                                             score_tensors(p), p->anchor, p->ema_gamma, s), "score launch");
+                                             score_tensors(p), anchor_bits(p), p->ema_gamma, s), "score launch");
     if (st != TF_OK) return st;
     mark(ctx, slot, 1, s);
     st = dev(ctx, tf::launch_fuse(d, p->fusion, sk, sv, fused, s), "fuse launch");
@@ -318,7 +321,7 @@ tf_status tf_score(tf_ctx* ctx, const tf_params* p, const void* K, const void* V
     char* base = (char*)ws;
     float* sk = sim_k ? sim_k : (float*)(base + w.sim_k);
     float* sv = sim_v ? sim_v : (float*)(base + w.sim_v);
-    st = dev(ctx, tf::launch_score(d, p->dtype, K, V, sk, sv, (float*)(base + w.seg_tot), score_tensors(p), p->anchor, p->ema_gamma, s), "score launch");
+    st = dev(ctx, tf::launch_score(d, p->dtype, K, V, sk, sv, (float*)(base + w.seg_tot), score_tensors(p), anchor_bits(p), p->ema_gamma, s), "score launch");
     if (st != TF_OK) return st;
     return dev(ctx, tf::launch_fuse(d, p->fusion, sk, sv, fused, s), "fuse launch");
 }
@@ -415,7 +418,7 @@ tf_status tf_filtered_attention_online(tf_ctx* ctx, const tf_params* p, float et
     float* sk = (float*)(base + w.sim_k);
     float* sv = (float*)(base + w.sim_v);
     st = dev(ctx, tf::launch_score(d, p->dtype, K, V, sk, sv, (float*)(base + w.seg_tot),
-                                   score_tensors(p), p->anchor, p->ema_gamma, s), "score launch");
+                                   score_tensors(p), anchor_bits(p), p->ema_gamma, s), "score launch");
     if (st != TF_OK) return st;
     st = dev(ctx, tf::launch_fuse(d, p->fusion, sk, sv, fused, s), "fuse launch");
     if (st != TF_OK) return st;
@@ -468,7 +471,7 @@ tf_status tf_decode_prefill(tf_ctx* ctx, const tf_params* p, float eta, float ta
     float* sk = (float*)(base + w.sim_k);
     float* sv = (float*)(base + w.sim_v);
     st = dev(ctx, tf::launch_score(d, p->dtype, K, V, sk, sv, (float*)(base + w.seg_tot),
-                                   score_tensors(p), p->anchor, p->ema_gamma, s), "score launch");
+                                   score_tensors(p), anchor_bits(p), p->ema_gamma, s), "score launch");
     if (st != TF_OK) return st;
     st = dev(ctx, tf::launch_fuse(d, p->fusion, sk, sv, fused, s), "fuse launch");
     if (st != TF_OK) return st;

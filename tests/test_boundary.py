@@ -33,7 +33,7 @@ def test_params_struct_matches_header_layout():
     assert ctypes.sizeof(B.tf_params) == 128
     assert B.tf_params.q_stride.offset == 24 and B.tf_params.prune_ratio.offset == 96
     assert B.tf_params.softmax_scale.offset == 112 and B.tf_params.anchor.offset == 116
-    assert B.tf_params.ema_gamma.offset == 120 and B.tf_params.reserved.offset == 124
+    assert B.tf_params.ema_gamma.offset == 120 and B.tf_params.anchor_inclusive.offset == 124
 
 
 def test_keep_count_host(golden_dir):
@@ -68,7 +68,7 @@ def test_workspace_bytes_and_shape_validation():
     assert bad(dtype=7) == 0
     assert bad(fusion=4) == 0
     assert bad(warmup=-1) == 0
-    assert bad(reserved=1) == 0
+    assert bad(anchor_inclusive=2) == 0
     assert bad(anchor=2) == 0
     assert bad(anchor=B.TF_ANCHOR_EMA, ema_gamma=1.0) == 0
     assert bad(anchor=B.TF_ANCHOR_EMA, ema_gamma=-0.1) == 0

@@ -33,11 +33,11 @@ def _say(msg):
 
 
 def gpu_decode(ctx, q, k, v, target, eta, tau0, W, capacity, fusion=B.TF_FUSE_EQ2, scale=0.0,
-               ema_gamma=None, alloc_capacity=None):
+               ema_gamma=None, alloc_capacity=None, inclusive=False):
     """All n tokens through tf_decode_step.  Returns (buffers, O [n,B,Hq,d], skip [n,B], fused [n,B])."""
     Bn, Hq, n, d = q.shape
     p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, target, W, fusion, scale,
-                      ema_gamma=ema_gamma)
+                      ema_gamma=ema_gamma, anchor_inclusive=inclusive)
     buf = B.DecodeBuffers(p, alloc_capacity or capacity)
     buf.state.capacity = capacity
     buf.k_cache.fill_(-77.0)
@@ -56,15 +56,16 @@ def gpu_decode(ctx, q, k, v, target, eta, tau0, W, capacity, fusion=B.TF_FUSE_EQ
 
 
 def check_decode(ctx, q, k, v, target, eta, tau0, W, fusion=B.TF_FUSE_EQ2, scale=0.0,
-                 ema_gamma=None, capacity=None):
+                 ema_gamma=None, capacity=None, inclusive=False):
     Bn, Hq, n, d = q.shape
     Hkv = k.shape[1]
     capacity = capacity or n
     g32 = None if ema_gamma is None else float(np.float32(ema_gamma))   # the value the library sees
     buf, O_g, skip_g, fused_g = gpu_decode(ctx, q, k, v, target, eta, tau0, W, capacity, fusion,
-                                           scale, ema_gamma)
+                                           scale, ema_gamma, inclusive=inclusive)
     assert not np.isnan(O_g).any() and not np.isnan(fused_g).any() and skip_g.max() <= 1
-    st = oracle.DecodeState(Bn, Hq, Hkv, d, capacity, target, eta, tau0, W, fusion, scale, g32)
+    st = oracle.DecodeState(Bn, Hq, Hkv, d, capacity, target, eta, tau0, W, fusion, scale, g32,
+                            inclusive=inclusive)
     qf, kf, vf = q.float().numpy(), k.float().numpy(), v.float().numpy()
     worst = 0.0
     for t in range(n):
@@ -105,6 +106,15 @@ def test_decode_steps_match_oracle(ctx, case):
     skip = check_decode(ctx, q, k, v, target, eta, tau0, W, fusion, scale, gamma)
     if eta > 0:
         assert 0 < skip.sum() < skip.size                 # both branches were exercised
+
+
+@pytest.mark.parametrize("gamma", [None, 0.9])
+def test_decode_steps_anchor_including_the_token(ctx, gamma):
+    _say("decode inclusive %s" % gamma)
+    w = synth.scaled(synth.workload(0), batch=2, seq=250, n_q_heads=4, n_kv_heads=2, dtype="bf16")
+    q, k, v, _ = synth.make_qkv(w)
+    # scores are higher when the token is part of its own anchor: a higher starting threshold
+    check_decode(ctx, q, k, v, 0.5, 0.05, 0.9, 4, ema_gamma=gamma, inclusive=True)
 
 
 def test_decode_first_token_and_all_skipped_after_warmup(ctx):

@@ -154,6 +154,32 @@ def test_score_parity_incremental_anchor(ctx, shape):
         assert_scores_close(buf.fused.cpu().numpy(), oracle.fuse(ck, cv, mode), "fused mode %d" % mode)
 
 
+@pytest.mark.parametrize("shape", [
+    # (dtype, B, Hq, Hkv, n, gamma or None): one segment and several, both anchor kinds
+    ("f32", 1, 4, 4, 1, None), ("f32", 2, 4, 2, 300, None), ("bf16", 2, 8, 2, 1000, 0.9),
+    ("bf16", 1, 32, 8, 4133, None), ("bf16", 1, 8, 2, 6000, 0.99), ("bf16", 4, 64, 64, 600, None),
+    ("bf16", 2, 8, 8, 700, 0.0),
+])
+def test_score_parity_anchor_including_the_token(ctx, shape):
+    """The other reading of Algorithm 1: the anchor a token is compared with already holds it."""
+    dt, Bn, Hq, Hkv, n, gamma = shape
+    _say("score inclusive %s" % (shape,))
+    q, k, v, _ = synth.make_random_qkv(Bn, Hq, Hkv, n, 128, dtype=dt, seed=500 + n)
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.5, ema_gamma=gamma, anchor_inclusive=True)
+    buf = B.Buffers(p, "cuda:0", with_sims=True)
+    if gamma is None:
+        ck, cv = oracle.anchor_cosine(k, inclusive=True), oracle.anchor_cosine(v, inclusive=True)
+    else:
+        ck = oracle.anchor_cosine_ema(k, gamma, inclusive=True)
+        cv = oracle.anchor_cosine_ema(v, gamma, inclusive=True)
+    ctx.tf_score(p, k.cuda(), v.cuda(), buf.fused, buf.sim_k, buf.sim_v, buf.ws)
+    torch.cuda.synchronize()
+    assert_scores_close(buf.sim_k.cpu().numpy(), ck, "sim_k")
+    assert_scores_close(buf.sim_v.cpu().numpy(), cv, "sim_v")
+    assert_scores_close(buf.fused.cpu().numpy(), oracle.fuse(ck, cv), "fused")
+    assert np.all(np.abs(buf.sim_k.cpu().numpy()[:, :, 0] - 1) <= 1e-6)    # a token against itself
+
+
 def test_whole_path_incremental_anchor(ctx):
     _say("whole path ema")
     w = synth.scaled(synth.workload(1), batch=2, seq=1800, n_q_heads=8, n_kv_heads=8)
