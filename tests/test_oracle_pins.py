@@ -615,3 +615,13 @@ def test_inclusive_decode_steps_reduce_to_the_batched_scores():
             st0.step(q[:, :, t], k[:, :, t], v[:, :, t])
             st1.step(q[:, :, t], k[:, :, t], v[:, :, t])
         np.testing.assert_array_equal(st0.anchor_k, st1.anchor_k)
+
+
+def test_anchor_state_footprint_matches_the_papers_figure():
+    # Section 3.2: one anchor key and one anchor value per layer, one vector per head, about
+    # 800 KB in total.  LLaMA-2-13B (40 layers, 40 heads of 128) in 16-bit storage:
+    assert 2 * 40 * 40 * 128 * 2 == 800 * 1024
+    # the per-layer state of the per-token form has exactly that structure (per batch row)
+    st = oracle.DecodeState(1, 40, 40, 128, 4, 0.5, 0.02, 0.5)
+    assert st.anchor_k.shape == st.anchor_v.shape == (1, 40, 128)
+    assert 40 * (st.anchor_k.size + st.anchor_v.size) * 2 == 800 * 1024
