@@ -459,6 +459,8 @@ tf_status tf_decode_prefill(tf_ctx* ctx, const tf_params* p, float eta, float ta
     if (st != TF_OK) return st;
     if (state->capacity < p->seq)
         return fail(ctx, TF_ERR_INVALID_ARG, "the caches hold %d rows, the prompt may keep %d", state->capacity, p->seq);
+    if ((int64_t)p->batch * p->n_kv_heads > 65535)
+        return fail(ctx, TF_ERR_UNSUPPORTED, "batch * n_kv_heads above 65535 is not supported by the hand-off");
     if (!Q || !K || !V || !O || !keep || !kept_idx || !count || !fused)
         return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V, O, keep, kept_idx, count and fused must not be NULL");
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O))
