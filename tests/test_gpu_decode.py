@@ -317,3 +317,49 @@ def test_prefill_rejects_caches_shorter_than_the_prompt(ctx):
     with pytest.raises(B.TokfiltError):
         ctx.tf_decode_prefill(p, 0.02, 0.5, buf.state, q.cuda(), k.cuda(), v.cuda(), bb.keep, idx, cnt,
                               bb.fused, bb.O, bb.ws)
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_prefill_strided_layout_equals_contiguous(ctx, dt):
+    """[B, n, H, d] storage of the prompt through the stride arguments: identical outputs, the
+    same decoding state, and the same next decoding step as with [B, H, n, d] storage."""
+    _say("prefill strided %s" % dt)
+    Bn, Hq, Hkv, n, d = 2, 4, 2, 333, 128
+    q, k, v, _ = synth.make_random_qkv(Bn, Hq, Hkv, n + 1, d, dtype=dt, seed=77)
+    eta, tau0 = 0.05, 0.1
+    results = []
+    for strided in (False, True):
+        qp, kp, vp = (x[:, :, :n].contiguous() for x in (q, k, v))
+        if strided:
+            qd, kd, vd = (x.permute(0, 2, 1, 3).contiguous().cuda() for x in (qp, kp, vp))
+            p = B.make_params(tuple(qp.shape), tuple(kp.shape), q.dtype, 0.5, 2, ema_gamma=0.9,
+                              q_stride=(n * Hq * d, d, Hq * d), kv_stride=(n * Hkv * d, d, Hkv * d),
+                              o_stride=(n * Hq * d, d, Hq * d))
+            O = torch.empty((Bn, n, Hq, d), dtype=q.dtype, device="cuda:0")
+        else:
+            qd, kd, vd = qp.cuda(), kp.cuda(), vp.cuda()
+            p = B.make_params(tuple(qp.shape), tuple(kp.shape), q.dtype, 0.5, 2, ema_gamma=0.9)
+            O = torch.empty((Bn, Hq, n, d), dtype=q.dtype, device="cuda:0")
+        buf = B.DecodeBuffers(p, n + 1)
+        bb = B.Buffers(p, "cuda:0")
+        idx = torch.full((Bn, n), -7, dtype=torch.int32, device="cuda:0")
+        cnt = torch.zeros((Bn,), dtype=torch.int32, device="cuda:0")
+        ctx.tf_decode_prefill(p, eta, tau0, buf.state, qd, kd, vd, bb.keep, idx, cnt, bb.fused, O, bb.ws)
+        ctx.tf_decode_step(p, eta, buf.state, q[:, :, n].contiguous().cuda(), k[:, :, n].contiguous().cuda(),
+                           v[:, :, n].contiguous().cuda(), buf.o, buf.skip, buf.fused, buf.ws)
+        torch.cuda.synchronize()
+        c = cnt.cpu()
+        clen = buf.cache_len.cpu()                         # after the decoded token
+        results.append(dict(
+            O=(O.permute(0, 2, 1, 3) if strided else O).cpu(), keep=bb.keep.cpu(), fused=bb.fused.cpu(),
+            cnt=c, tau=buf.tau.cpu(), anchor_k=buf.anchor_k.cpu(), anchor_v=buf.anchor_v.cpu(),
+            clen=clen,
+            kc=[buf.k_cache[b, :, :int(clen[b])].cpu() for b in range(Bn)],
+            vc=[buf.v_cache[b, :, :int(clen[b])].cpu() for b in range(Bn)],
+            o=buf.o.cpu(), skip=buf.skip.cpu(), f1=buf.fused.cpu(), seen=buf.seen.cpu()))
+    a, b_ = results
+    for name in ("O", "keep", "fused", "cnt", "clen", "tau", "anchor_k", "anchor_v", "o", "skip", "f1", "seen"):
+        assert torch.equal(a[name], b_[name]), name
+    for x, y in zip(a["kc"] + a["vc"], b_["kc"] + b_["vc"]):
+        assert torch.equal(x, y)
+    assert 0 < int(a["cnt"].sum()) < Bn * n
