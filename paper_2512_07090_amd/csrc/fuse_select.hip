@@ -315,9 +315,9 @@ __global__ __launch_bounds__(kSelThreads) void select_compact_kernel(
 //   tau <- fma(eta, (float)skipped * (1 / t) - target, tau);  skip iff t >= W and S_t > tau,
 // all in float so that the result is reproducible bit for bit.  One workgroup per batch row
 // walks the row in chunks of kOnChunk tokens: all threads stage the chunk's scores and the
-// reciprocals 1 / t in LDS, thread 0 runs the recurrence (both candidates of the next threshold,
-// for "skipped" and "kept", are formed next to the comparison, so that the chain from one token
-// to the next is a compare and a select), then all threads compact the chunk's flags.
+// reciprocals 1 / t in LDS, thread 0 runs the recurrence and leaves the running count of
+// skipped tokens in place of the scores, then all threads read the decisions off the counts
+// and compact them.
 constexpr int kOnChunk = 4096;
 
 __global__ __launch_bounds__(kSelThreads) void select_online_kernel(
@@ -330,8 +330,8 @@ __global__ __launch_bounds__(kSelThreads) void select_online_kernel(
 #pragma clang fp contract(off)
     __shared__ __attribute__((aligned(16))) float s_lds[kOnChunk];
     __shared__ __attribute__((aligned(16))) float inv_lds[kOnChunk];
-    __shared__ __attribute__((aligned(16))) uint8_t flag_lds[kOnChunk];
     __shared__ int scan_lds[kSelWaves + 1];
+    __shared__ float skip_base;  // skipped tokens before the current chunk
 
     const int b = blockIdx.x;
     const int tid = threadIdx.x;
@@ -356,30 +356,33 @@ __global__ __launch_bounds__(kSelThreads) void select_online_kernel(
         __syncthreads();
         if (tid == 0) {
             // eight tokens at a time: their scores and reciprocals are fetched together (two
-            // 16-byte LDS reads each), the eight steps of the chain then run from registers and
-            // the eight flags leave as one 8-byte store
+            // 16-byte LDS reads each) and the eight steps of the chain run from registers.  A
+            // step is five dependent operations (compare, select, multiply, subtract, fma); a
+            // lone wave waits about as long for a dependent result as it takes to issue two
+            // instructions, so forming both outcomes ahead of the comparison (a shorter chain,
+            // twice the instructions) measured slower than this plain form.  The running count
+            // of skipped tokens replaces the scores in LDS: the other threads read the
+            // decisions off it afterwards (a token was skipped iff the count moved).
+            skip_base = skipped;
             for (int i0 = 0; i0 < len; i0 += 8) {
-                float sv[8], iv[8];
+                float sv[8], iv[8], sk[8];
                 *reinterpret_cast<float4*>(&sv[0]) = *reinterpret_cast<const float4*>(&s_lds[i0]);
                 *reinterpret_cast<float4*>(&sv[4]) = *reinterpret_cast<const float4*>(&s_lds[i0 + 4]);
                 *reinterpret_cast<float4*>(&iv[0]) = *reinterpret_cast<const float4*>(&inv_lds[i0]);
                 *reinterpret_cast<float4*>(&iv[4]) = *reinterpret_cast<const float4*>(&inv_lds[i0 + 4]);
                 float tau_in[8];  // the threshold each of the eight tokens is judged with
-                unsigned long long flags = 0;
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    // thresholds of the next token for both outcomes of this one
-                    const float s1 = skipped + 1.f;
-                    const float p_k = skipped * iv[u], p_s = s1 * iv[u];
-                    const float tau_k = fmaf(eta, p_k - target, tau);
-                    const float tau_s = fmaf(eta, p_s - target, tau);
-                    const bool skip = sv[u] > tau;
-                    flags |= (unsigned long long)(skip ? 0 : 1) << (8 * u);
                     tau_in[u] = tau;
-                    tau = skip ? tau_s : tau_k;
-                    skipped = skip ? s1 : skipped;
+                    const float s1 = skipped + 1.f;
+                    skipped = sv[u] > tau ? s1 : skipped;
+                    const float p_next = skipped * iv[u];
+                    const float diff = p_next - target;
+                    tau = fmaf(eta, diff, tau);
+                    sk[u] = skipped;
                 }
-                *reinterpret_cast<unsigned long long*>(&flag_lds[i0]) = flags;
+                *reinterpret_cast<float4*>(&s_lds[i0]) = *reinterpret_cast<const float4*>(&sk[0]);
+                *reinterpret_cast<float4*>(&s_lds[i0 + 4]) = *reinterpret_cast<const float4*>(&sk[4]);
                 if (i0 + 8 >= len) {  // the group that holds the row's last token
 #pragma unroll
                     for (int u = 0; u < 8; ++u)
@@ -390,7 +393,8 @@ __global__ __launch_bounds__(kSelThreads) void select_online_kernel(
         __syncthreads();
         for (int i0 = 0; i0 < len; i0 += kSelThreads) {
             const int i = i0 + tid;
-            const int flag = i < len ? flag_lds[i] : 0;
+            // kept iff the count of skipped tokens did not move at token i
+            const int flag = i < len ? (s_lds[i] == (i > 0 ? s_lds[i - 1] : skip_base)) : 0;
             int total;
             const int pos = base + block_excl_scan(flag, scan_lds, &total);
             base += total;
