@@ -363,3 +363,52 @@ def test_prefill_strided_layout_equals_contiguous(ctx, dt):
     for x, y in zip(a["kc"] + a["vc"], b_["kc"] + b_["vc"]):
         assert torch.equal(x, y)
     assert 0 < int(a["cnt"].sum()) < Bn * n
+
+
+def test_decode_step_replays_from_a_captured_graph(ctx):
+    """tf_decode_step allocates nothing and never synchronises: one captured step, replayed once
+    per token with the token copied into fixed input buffers, must give what the eager loop
+    gives, bit for bit (the serving pattern: one graph launch per token)."""
+    _say("decode graph replay")
+    w = synth.scaled(synth.workload(0), batch=2, seq=120, n_q_heads=8, n_kv_heads=4, dtype="bf16")
+    q, k, v, _ = synth.make_qkv(w)
+    Bn, Hq, n, d = q.shape
+    target, eta, tau0, W = 0.5, 0.05, 0.5, 4
+    buf_e, O_e, skip_e, fused_e = gpu_decode(ctx, q, k, v, target, eta, tau0, W, capacity=n)
+
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, target, W)
+    buf = B.DecodeBuffers(p, n)
+    qs = q.permute(2, 0, 1, 3).contiguous().cuda()
+    ks = k.permute(2, 0, 1, 3).contiguous().cuda()
+    vs = v.permute(2, 0, 1, 3).contiguous().cuda()
+    q_in, k_in, v_in = torch.empty_like(qs[0]), torch.empty_like(ks[0]), torch.empty_like(vs[0])
+
+    def step():
+        ctx.tf_decode_step(p, eta, buf.state, q_in, k_in, v_in, buf.o, buf.skip, buf.fused, buf.ws)
+    # warm the call on a side stream (as capture requires), then start the sequence afresh
+    ctx.tf_decode_init(p, buf.state, tau0)
+    q_in.copy_(qs[0]); k_in.copy_(ks[0]); v_in.copy_(vs[0])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step()
+    ctx.tf_decode_init(p, buf.state, tau0)
+    torch.cuda.synchronize()
+    for t in range(n):
+        q_in.copy_(qs[t]); k_in.copy_(ks[t]); v_in.copy_(vs[t])
+        buf.ws.fill_(0xFF)                                   # stale partial results
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(buf.skip.cpu().numpy(), skip_e[t]), "decision, token %d" % t
+        assert np.array_equal(buf.fused.cpu().numpy(), fused_e[t]), "score, token %d" % t
+        assert np.array_equal(buf.o.float().cpu().numpy().astype(np.float64), O_e[t]), "output, token %d" % t
+    for name in ("seen", "skipped", "cache_len", "tau", "anchor_k", "anchor_v"):
+        assert torch.equal(getattr(buf, name), getattr(buf_e, name)), name
+    for b in range(Bn):
+        c = int(buf.cache_len[b])
+        assert torch.equal(buf.k_cache[b, :, :c], buf_e.k_cache[b, :, :c])
+        assert torch.equal(buf.v_cache[b, :, :c], buf_e.v_cache[b, :, :c])
