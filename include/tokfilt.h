@@ -8,6 +8,18 @@
  * most redundant tokens are filtered at a target ratio, and causal attention runs over the
  * kept tokens only, filtered tokens receiving a zero attention output (Section 3.2).
  *
+ * Groups of entry points
+ *   - batched, exact count:  tf_score, tf_select, tf_attend, tf_filtered_attention
+ *   - batched, online threshold (Section 3.3, Eq. 4):  tf_select_online, tf_attend_ragged,
+ *     tf_filtered_attention_online
+ *   - tail-focused layer schedule (Eq. 3):  tf_tail_schedule, tf_filtered_attention_layers
+ *   - one token at a time with caller-held state (Algorithm 1 as a call per token):
+ *     tf_decode_init, tf_decode_prefill, tf_decode_step
+ *   - measurement:  tf_stage_timing_*, tf_probe_*
+ * Variants selected through tf_params: the incremental anchor of Eq. 1 (anchor, ema_gamma), the
+ * anchor that includes the current token (anchor_inclusive), key-only / value-only scores and
+ * the two readings of Eq. 2 (fusion).
+ *
  * Conventions for every entry point
  *   - Pointers named Q, K, V, O, fused, sim_k, sim_v, keep, kept_idx, tau and ws are DEVICE
  *     pointers on the context's GPU.  `tf_params` and everything else is HOST memory.
