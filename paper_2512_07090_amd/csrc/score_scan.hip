@@ -10,6 +10,7 @@
 //   consecutive rows of the tile and 8 consecutive columns, so a 16-lane DPP row reads one
 //   full 256-byte (bf16) row per load and the three 128-long reductions of a row finish
 //   inside that DPP row.
+//   Two tiles are in flight while a third is processed (three register buffers).
 //   Per tile: (1) per-thread column totals of its 8 rows; (2) exclusive scan of those totals
 //   over the 16 row groups (bpermute inside a wave, 2 KB of LDS across the 4 waves);
 //   (3) each thread replays its 8 rows against its running prefix.
@@ -179,8 +180,9 @@ __global__ __launch_bounds__(kThreads) void scan_score_kernel(
         carry[4] += b.x; carry[5] += b.y; carry[6] += b.z; carry[7] += b.w;
     }
 
-    Row8<T> buf0[kR], buf1[kR];
+    Row8<T> buf0[kR], buf1[kR], buf2[kR];
     load_tile(buf0, X, s_t, t_begin + rg * kR, t_end, 8 * l);
+    load_tile(buf1, X, s_t, t_begin + kTile + rg * kR, t_end, 8 * l);
 
     int parity = 0;
     auto process = [&](const Row8<T>* rows, int t0, bool first_tile) {
@@ -303,13 +305,16 @@ __global__ __launch_bounds__(kThreads) void scan_score_kernel(
         }
     };
 
-    for (int t0 = t_begin; t0 < t_end; t0 += 2 * kTile) {
-        const bool more1 = t0 + kTile < t_end;
-        if (more1) load_tile(buf1, X, s_t, t0 + kTile + rg * kR, t_end, 8 * l);
+    // two tiles in flight while a third is processed (rows past the end load as zeros)
+    for (int t0 = t_begin; t0 < t_end; t0 += 3 * kTile) {
+        load_tile(buf2, X, s_t, t0 + 2 * kTile + rg * kR, t_end, 8 * l);
         process(buf0, t0, t0 == 0);
-        if (!more1) break;
-        if (t0 + 2 * kTile < t_end) load_tile(buf0, X, s_t, t0 + 2 * kTile + rg * kR, t_end, 8 * l);
+        if (t0 + kTile >= t_end) break;
+        load_tile(buf0, X, s_t, t0 + 3 * kTile + rg * kR, t_end, 8 * l);
         process(buf1, t0 + kTile, false);
+        if (t0 + 2 * kTile >= t_end) break;
+        load_tile(buf1, X, s_t, t0 + 4 * kTile + rg * kR, t_end, 8 * l);
+        process(buf2, t0 + 2 * kTile, false);
     }
 }
 
