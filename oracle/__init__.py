@@ -45,7 +45,7 @@ def _load():
         lib.tfo_tail_schedule.argtypes = [i64, dbl, dbl, vp]
         lib.tfo_tail_schedule.restype = i64
         flt = ctypes.c_float
-        lib.tfo_select_online.argtypes = [vp, i64, i64, i64, flt, flt, flt, vp, vp, vp, vp]
+        lib.tfo_select_online.argtypes = [vp, i64, i64, i64, flt, flt, flt, vp, vp, vp, vp, vp]
         lib.tfo_keep_count.restype = i64
         lib.tfo_select.argtypes = [vp, i64, i64, i64, i64, vp, vp, vp]
         lib.tfo_attend.argtypes = [vp, vp, vp, i64, i64, i64, i64, i64, vp, i64, dbl, vp]
@@ -146,19 +146,24 @@ def _scale(d, scale):
     return float(scale) if scale else 1.0 / float(np.sqrt(d))
 
 
-def select_online(scores, target: float, eta: float, tau0: float, warmup: int = 1):
+def select_online(scores, target: float, eta: float, tau0: float, warmup: int = 1,
+                  return_trace: bool = False):
     """Online keep decision with the adaptive threshold of Eq. 4.  scores: [B, n] (rounded to
     float32 first).  Returns keep [B, n] uint8, kept_idx [B, n] int32 (padded with -1),
-    count [B] int32, tau [B] float32 (threshold after the last token)."""
+    count [B] int32, tau [B] float32 (threshold after the last token); with return_trace also
+    the threshold every token was judged with, [B, n] float32."""
     s32 = np.ascontiguousarray(np.asarray(scores, dtype=np.float64).astype(np.float32))
     B, n = s32.shape
     keep = np.empty((B, n), dtype=np.uint8)
     idx = np.empty((B, n), dtype=np.int32)
     count = np.empty((B,), dtype=np.int32)
     tau = np.empty((B,), dtype=np.float32)
+    trace = np.empty((B, n), dtype=np.float32) if return_trace else None
     _load().tfo_select_online(_p(s32), B, n, int(warmup), ctypes.c_float(target),
                               ctypes.c_float(eta), ctypes.c_float(tau0), _p(keep), _p(idx),
-                              _p(count), _p(tau))
+                              _p(count), _p(tau), _p(trace) if return_trace else None)
+    if return_trace:
+        return keep, idx, count, tau, trace
     return keep, idx, count, tau
 
 

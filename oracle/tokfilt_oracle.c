@@ -304,10 +304,10 @@ void tfo_select(const float *S32, int64_t B, int64_t n, int64_t m, int64_t W, ui
  * float; P_current = (float)skipped * (1.0f / (float)t); tau = fmaf(eta, P_current - target, tau).
  * S32: [B][n].  keep: [B][n] 0/1.  kept_idx: [B][n], the first count[b] entries of row b are the
  * kept positions ascending, the rest is -1.  count: [B].  tau_out: [B], the threshold after the
- * last token. */
+ * last token.  tau_trace (may be NULL): [B][n], the threshold each token was judged with. */
 void tfo_select_online(const float *S32, int64_t B, int64_t n, int64_t W, float target, float eta,
                        float tau0, uint8_t *keep, int32_t *kept_idx, int32_t *count,
-                       float *tau_out)
+                       float *tau_out, float *tau_trace)
 {
     for (int64_t b = 0; b < B; ++b) {
         const float *s = S32 + b * n;
@@ -318,6 +318,8 @@ void tfo_select_online(const float *S32, int64_t B, int64_t n, int64_t W, float 
             float p_current = (float)skipped * inv_t;
             float diff = p_current - target;
             tau = fmaf(eta, diff, tau);
+            if (tau_trace)
+                tau_trace[b * n + t] = tau;
             int skip = (t >= W) && (s[t] > tau);
             keep[b * n + t] = (uint8_t)!skip;
             if (skip)

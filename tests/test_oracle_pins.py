@@ -326,6 +326,10 @@ def test_online_threshold_golden_worked_example(golden_dir):
     for t in range(5):
         _, _, _, tau_t = oracle.select_online(S[:, :t + 1], 0.5, 0.1, 0.5, 1)
         assert abs(float(tau_t[0]) - tab[t, 3]) <= 1e-6
+    # the per-token trace is the same list: the threshold each token was judged with
+    _, _, _, _, trace = oracle.select_online(S, 0.5, 0.1, 0.5, 1, return_trace=True)
+    assert np.all(np.abs(trace[0] - tab[:, 3]) <= 1e-6)
+    assert np.array_equal(keep[0] == 0, (S[0].astype(np.float32) > trace[0]) & (np.arange(5) >= 1))
 
 
 def test_online_threshold_closed_forms_and_feedback():
