@@ -81,8 +81,8 @@ typedef enum {
 typedef enum { TF_ANCHOR_MEAN = 0, TF_ANCHOR_EMA = 1 } tf_anchor;
 
 typedef struct {
-    int32_t batch;
-    int32_t n_q_heads;
+    int32_t batch;         /* 1 .. 65535 */
+    int32_t n_q_heads;     /* 1 .. 65535 */
     int32_t n_kv_heads;    /* n_q_heads % n_kv_heads == 0 (grouped-query attention) */
     int32_t seq;           /* n >= 1 */
     int32_t head_dim;      /* only 128 is supported */
@@ -174,12 +174,15 @@ tf_status tf_attend(tf_ctx *ctx, const tf_params *p, const void *Q, const void *
  *   kept_idx  out [batch][seq] int32: the first count[b] entries of row b are the kept positions
  *                 ascending, the rest is -1
  *   count     out [batch] int32
- *   tau       out [batch] float (optional): the threshold the last token was judged with */
+ *   tau       out [batch] float (optional): the threshold the last token was judged with
+ * p->seq up to 2^24 (the count of skipped tokens is carried in a float). */
 tf_status tf_select_online(tf_ctx *ctx, const tf_params *p, float eta, float tau0,
                            const float *fused, uint8_t *keep, int32_t *kept_idx, int32_t *count,
                            float *tau, void *ws, size_t ws_bytes, void *stream);
 
-/* tf_attend for kept sets whose size differs from row to row: kept_idx is [batch][seq], row b
+/* tf_attend (Section 3.2: zero attention output for a skipped token, ordinary causal attention
+ * for the others) for kept sets whose size differs from row to row, as the online decision of
+ * Section 3.3 / Eq. 4 produces them: kept_idx is [batch][seq], row b
  * holds count[b] strictly ascending positions (what follows them is not read); count is a
  * DEVICE array [batch], 0 <= count[b] <= seq.  A row with count 0 gets an all-zero output. */
 tf_status tf_attend_ragged(tf_ctx *ctx, const tf_params *p, const void *Q, const void *K,
@@ -194,8 +197,11 @@ tf_status tf_filtered_attention_online(tf_ctx *ctx, const tf_params *p, float et
                                        float *fused, float *tau, void *O, void *ws,
                                        size_t ws_bytes, void *stream);
 
-/* The whole path: tf_score -> tf_select -> tf_attend on one stream, no host round trip.
- * Outputs as in the three calls above; tau may be NULL. */
+/* The whole layer as Algorithm 1 states it, for every token of every batch row at once: anchor
+ * and per-head cosines (Section 3.2), variance-aware fusion (Eq. 2), the skip decision at the
+ * target ratio, and attention for the tokens that are not skipped with a zero attention output
+ * for those that are (Section 3.2).  tf_score -> tf_select -> tf_attend on one stream, no host
+ * round trip.  Outputs as in the three calls above; tau may be NULL. */
 tf_status tf_filtered_attention(tf_ctx *ctx, const tf_params *p, const void *Q, const void *K,
                                 const void *V, uint8_t *keep, int32_t *kept_idx, float *fused,
                                 float *tau, void *O, void *ws, size_t ws_bytes, void *stream);
@@ -264,15 +270,21 @@ tf_status tf_decode_step(tf_ctx *ctx, const tf_params *p, float eta, const tf_de
 
 /* Tail-focused layer schedule (Section 3.3, Eq. 3), host side: to meet the global budget
  * p_global in [0, 1], the last ceil(tail_fraction * n_layers) layers (0 < tail_fraction <= 1)
- * are pruned at p_global / tail_fraction (not above 1), the others at 0.
+ * are pruned at p_global / tail_fraction (capped at 1: such a layer skips the attention of all
+ * its tokens, which tf_filtered_attention_layers accepts), the others at 0.
  * ratios: host array [n_layers]; *n_tail (may be NULL): number of selected layers. */
 tf_status tf_tail_schedule(int32_t n_layers, double p_global, double tail_fraction,
                            double *ratios, int32_t *n_tail);
 
-/* Tail-focused multi-layer driver (Section 3.3): the whole path on n_layers layers of one shape
- * `p`, layer l at pruning ratio ratios[l] (p->prune_ratio is ignored; every ratio in [0, 1)).
+/* Tail-focused multi-layer driver (Section 3.3, Eq. 3: the selected layers run the filter of
+ * Algorithm 1 at P_tail, the others are left dense; a skipped token's attention output is zero,
+ * Section 3.2): the whole path on n_layers layers of one shape `p`, layer l at pruning ratio
+ * ratios[l] (p->prune_ratio is ignored; every ratio in [0, 1], as tf_tail_schedule produces).
  * A layer at ratio 0 does no scoring: all its tokens are kept (keep = 1, kept_idx = 0..seq-1,
- * tau = +inf, fused not written) and it runs plain causal attention.  Q, K, V, O, keep,
+ * tau = +inf, fused not written) and it runs plain causal attention.  A layer at ratio 1 (the
+ * schedule's cap, e.g. a 50 % budget on the last half of the layers) skips the attention of
+ * every token: keep = 0, tau = -inf, O all zero, kept_idx and fused neither read nor written
+ * (their pointers may be NULL).  Q, K, V, O, keep,
  * kept_idx, fused, tau: host arrays of n_layers device pointers, each as in
  * tf_filtered_attention (kept_idx[l] holds [batch][tf_keep_count(seq, ratios[l])]); tau may be
  * NULL.  One workspace of tf_workspace_bytes(p) serves all layers in stream order. */

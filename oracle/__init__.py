@@ -38,6 +38,7 @@ def _load():
         lib = ctypes.CDLL(build())
         i64, dbl, vp = ctypes.c_int64, ctypes.c_double, ctypes.c_void_p
         lib.tfo_num_threads.restype = ctypes.c_int
+        lib.tfo_set_num_threads.argtypes = [ctypes.c_int]
         lib.tfo_anchor_cosine.argtypes = [vp, i64, i64, i64, i64, ctypes.c_int, vp, vp]
         lib.tfo_anchor_cosine_ema.argtypes = [vp, i64, i64, i64, i64, dbl, ctypes.c_int, vp, vp]
         lib.tfo_fuse.argtypes = [vp, vp, i64, i64, i64, ctypes.c_int, vp, vp]
@@ -61,6 +62,11 @@ def _load():
 
 def num_threads() -> int:
     return int(_load().tfo_num_threads())
+
+
+def set_num_threads(n: int) -> None:
+    """How many threads the loops over (batch, head) use from now on."""
+    _load().tfo_set_num_threads(int(n))
 
 
 def _f32(x) -> np.ndarray:

@@ -62,6 +62,16 @@ int tfo_num_threads(void)
 #endif
 }
 
+/* Threads the parallel loops over (batch, head) use from now on (for timing on one thread). */
+void tfo_set_num_threads(int n)
+{
+#ifdef _OPENMP
+    omp_set_num_threads(n < 1 ? 1 : n);
+#else
+    (void)n;
+#endif
+}
+
 /* Incremental anchor (Section 3.2, Eq. 1): Anchor <- gamma * Anchor + (1 - gamma) * x_current,
  * one anchor per (b, h), starting from zero.  inclusive = 0: row t is scored against the anchor
  * as it stands BEFORE row t is folded in (the reading "previous keys" of the exact mean, kept

@@ -498,6 +498,20 @@ hipError_t launch_keep_all(const Dims& d, uint8_t* keep, int32_t* kept_idx, floa
     return hipGetLastError();
 }
 
+__global__ void keep_none_kernel(int n, uint8_t* __restrict__ keep, float* __restrict__ tau)
+{
+    const int b = blockIdx.y;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) keep[(long long)b * n + i] = 0;
+    if (tau && i == 0) tau[b] = -INFINITY;
+}
+
+hipError_t launch_keep_none(const Dims& d, uint8_t* keep, float* tau, hipStream_t s)
+{
+    keep_none_kernel<<<dim3((d.n + 255) / 256, d.B), dim3(256), 0, s>>>(d.n, keep, tau);
+    return hipGetLastError();
+}
+
 hipError_t launch_mask_from_idx(const Dims& d, const int32_t* kept_idx, uint8_t* keep,
                                 const int32_t* counts, long long idx_stride, hipStream_t s)
 {

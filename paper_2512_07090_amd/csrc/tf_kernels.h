@@ -52,6 +52,8 @@ hipError_t launch_select_online(const Dims& d, int warmup, float target, float e
 // every token kept: keep = 1, kept_idx = 0 .. n-1, tau = +inf (tau may be null)
 hipError_t launch_keep_all(const Dims& d, uint8_t* keep, int32_t* kept_idx, float* tau,
                            hipStream_t s);
+// no token kept: keep = 0, tau = -inf (tau may be null)
+hipError_t launch_keep_none(const Dims& d, uint8_t* keep, float* tau, hipStream_t s);
 // keep mask from an index list (for callers that bring their own kept set)
 hipError_t launch_mask_from_idx(const Dims& d, const int32_t* kept_idx, uint8_t* keep,
                                 const int32_t* counts, long long idx_stride, hipStream_t s);

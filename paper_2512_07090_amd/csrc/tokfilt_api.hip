@@ -24,6 +24,7 @@ namespace {
 
 constexpr int kMaxTimedCalls = 256;
 constexpr int kMaxKvHeads = 128;  // LDS staging of the fusion kernel
+constexpr int kMaxOnlineSeq = 1 << 24;  // the online decision's float counter of skipped tokens is exact up to here
 
 tf_status fail(tf_ctx* c, tf_status s, const char* fmt, ...) __attribute__((format(printf, 3, 4)));
 tf_status fail(tf_ctx* c, tf_status s, const char* fmt, ...)
@@ -80,6 +81,10 @@ tf_status check_shape(const tf_params* p, const char** why)
     if (p->head_dim != tf::kHeadDim) { *why = "only head_dim 128 is supported"; return TF_ERR_UNSUPPORTED; }
     if (p->n_kv_heads > kMaxKvHeads) { *why = "more than 128 KV heads is not supported"; return TF_ERR_UNSUPPORTED; }
     if ((int64_t)p->batch * p->seq > (int64_t)1 << 30) { *why = "batch * seq too large"; return TF_ERR_UNSUPPORTED; }
+    // batch rows and query heads index the second and third grid dimension of some launches
+    if (p->batch > 65535 || p->n_q_heads > 65535) {
+        *why = "batch and n_q_heads above 65535 are not supported"; return TF_ERR_UNSUPPORTED;
+    }
     return TF_OK;
 }
 
@@ -371,6 +376,8 @@ tf_status tf_select_online(tf_ctx* ctx, const tf_params* p, float eta, float tau
         return fail(ctx, TF_ERR_INVALID_ARG, "fused, keep, kept_idx and count must not be NULL");
     if (!(eta >= 0.f) || isinf(eta) || isnan(tau0) || isinf(tau0))
         return fail(ctx, TF_ERR_INVALID_ARG, "eta must be finite and >= 0, tau0 finite");
+    if (p->seq > kMaxOnlineSeq)
+        return fail(ctx, TF_ERR_UNSUPPORTED, "the online decision counts skipped tokens in a float: seq above 2^24 is not supported");
     const tf::Dims d = make_dims(p, p->seq);
     return dev(ctx, tf::launch_select_online(d, p->warmup, (float)p->prune_ratio, eta, tau0, fused, keep,
                                              kept_idx, count, tau, (hipStream_t)stream),
@@ -412,6 +419,8 @@ tf_status tf_filtered_attention_online(tf_ctx* ctx, const tf_params* p, float et
         return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V and O must be 16-byte aligned");
     if (!(eta >= 0.f) || isinf(eta) || isnan(tau0) || isinf(tau0))
         return fail(ctx, TF_ERR_INVALID_ARG, "eta must be finite and >= 0, tau0 finite");
+    if (p->seq > kMaxOnlineSeq)
+        return fail(ctx, TF_ERR_UNSUPPORTED, "the online decision counts skipped tokens in a float: seq above 2^24 is not supported");
     const tf::Dims d = make_dims(p, p->seq);
     hipStream_t s = (hipStream_t)stream;
     char* base = (char*)ws;
@@ -467,6 +476,8 @@ tf_status tf_decode_prefill(tf_ctx* ctx, const tf_params* p, float eta, float ta
         return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V and O must be 16-byte aligned");
     if (!(eta >= 0.f) || isinf(eta) || isnan(tau0) || isinf(tau0))
         return fail(ctx, TF_ERR_INVALID_ARG, "eta must be finite and >= 0, tau0 finite");
+    if (p->seq > kMaxOnlineSeq)
+        return fail(ctx, TF_ERR_UNSUPPORTED, "the online decision counts skipped tokens in a float: seq above 2^24 is not supported");
     const tf::Dims d = make_dims(p, p->seq);
     hipStream_t s = (hipStream_t)stream;
     char* base = (char*)ws;
@@ -561,9 +572,10 @@ tf_status tf_filtered_attention_layers(tf_ctx* ctx, const tf_params* p, int32_t 
         return fail(ctx, TF_ERR_INVALID_ARG, "n_layers >= 1 and the ratio and pointer arrays are required");
     // everything is checked before the first launch
     for (int32_t l = 0; l < n_layers; ++l) {
-        if (!(ratios[l] >= 0.0 && ratios[l] < 1.0))
-            return fail(ctx, TF_ERR_INVALID_ARG, "ratio of layer %d must be in [0, 1)", l);
-        if (!Q[l] || !K[l] || !V[l] || !O[l] || !keep[l] || !kept_idx[l] || (ratios[l] > 0.0 && !fused[l]))
+        if (!(ratios[l] >= 0.0 && ratios[l] <= 1.0))
+            return fail(ctx, TF_ERR_INVALID_ARG, "ratio of layer %d must be in [0, 1]", l);
+        const bool scored = ratios[l] > 0.0 && ratios[l] < 1.0;
+        if (!Q[l] || !K[l] || !V[l] || !O[l] || !keep[l] || (ratios[l] < 1.0 && !kept_idx[l]) || (scored && !fused[l]))
             return fail(ctx, TF_ERR_INVALID_ARG, "a pointer of layer %d is NULL", l);
         if (misaligned(Q[l]) || misaligned(K[l]) || misaligned(V[l]) || misaligned(O[l]))
             return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V and O of layer %d must be 16-byte aligned", l);
@@ -573,7 +585,14 @@ tf_status tf_filtered_attention_layers(tf_ctx* ctx, const tf_params* p, int32_t 
         tf_params pl = *p;
         pl.prune_ratio = ratios[l];
         float* tau_l = tau ? tau[l] : nullptr;
-        if (tf_keep_count(p->seq, ratios[l]) == p->seq) {
+        if (ratios[l] >= 1.0) {
+            // the schedule's cap (P_global / Y reaching 1): the attention of every token of this
+            // layer is skipped, so no scoring, no kept token, an all-zero output
+            pl.prune_ratio = 0.0;
+            const tf::Dims d = make_dims(&pl, 0);
+            st = dev(ctx, tf::launch_keep_none(d, keep[l], tau_l, s), "keep-none launch");
+            if (st == TF_OK) st = dev(ctx, tf::launch_zero_filtered(d, p->dtype, keep[l], O[l], s), "zero-fill launch");
+        } else if (tf_keep_count(p->seq, ratios[l]) == p->seq) {
             // nothing to filter: no scoring, every token kept, plain causal attention
             const tf::Dims d = make_dims(&pl, p->seq);
             st = dev(ctx, tf::launch_keep_all(d, keep[l], kept_idx[l], tau_l, s), "keep-all launch");

@@ -212,6 +212,17 @@ def test_decode_full_size_bench_shape(ctx):
     np.testing.assert_array_equal(buf.tau.cpu().numpy(), tau_r)
     assert np.all(buf.overflow.cpu().numpy() == 0)
     assert np.all(O_g[skip_g == 1] == 0)
+    # end to end: against the oracle's decisions on the oracle's own scores, a row's masks are
+    # equal or first part at a token whose oracle score sits on its threshold
+    keep_o, _, _, _, trace = oracle.select_online(ref["fused"], target, eta, tau0, W, return_trace=True)
+    s32 = ref["fused"].astype(np.float32).astype(np.float64)
+    for b in range(Bn):
+        diff = np.nonzero((1 - skip_g.T)[b] != keep_o[b])[0]
+        if len(diff):
+            t = int(diff[0])
+            gap = abs(s32[b, t] - float(trace[b, t]))
+            _say("  row %d parts from the oracle's own mask at token %d, |score - threshold| %.2e" % (b, t, gap))
+            assert gap <= 1e-5, "row %d: first differing token %d is %.3e from its threshold" % (b, t, gap)
     rng = np.random.default_rng(3)
     rows = []
     for b in range(Bn):
