@@ -114,7 +114,9 @@ enum { TF_STAGE_SCORE = 0, TF_STAGE_FUSE = 1, TF_STAGE_SELECT = 2, TF_STAGE_COMP
 tf_status tf_create(tf_ctx **out, int device);
 void tf_destroy(tf_ctx *ctx);
 
-const char *tf_status_string(tf_status s);
+/* Name of a status code; any integer may be passed ("unknown status" for values that are not a
+ * tf_status). */
+const char *tf_status_string(int status);
 /* Text of the last error recorded on `ctx` ("" if none).  Owned by the context. */
 const char *tf_last_error(const tf_ctx *ctx);
 

@@ -35,6 +35,14 @@
 #include "tf_kernels.h"
 #include <algorithm>
 
+// build-time choice of the work decomposition (see the kernel)
+#ifndef TF_ATTEND_NW
+#define TF_ATTEND_NW 8
+#endif
+#ifndef TF_ATTEND_DEPTH
+#define TF_ATTEND_DEPTH 2
+#endif
+
 namespace tf {
 
 namespace {
@@ -44,7 +52,6 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int kBM = 256;                 // kept queries per workgroup
 constexpr int kBN = 64;                  // kept keys per tile
 constexpr int kKStr = kHeadDim + 8;      // K tile row stride, elements (272 B)
 constexpr int kVStr = kHeadDim + 32;     // V tile row stride, elements (320 B)
@@ -87,19 +94,43 @@ __device__ __forceinline__ Pos<4> load_pos(const int32_t* idx, int j, int step, 
     return Pos<4>{idx[min(j, last)], idx[min(j + step, last)], idx[min(j + 2 * step, last)],
                   idx[min(j + 3 * step, last)]};
 }
-__device__ __forceinline__ uint4 load16(const uint16_t* base, int pos, long long s_t)
+// One 16-byte chunk of the row at position `pos`: `base` is uniform over the workgroup (the
+// (batch, head) slice plus nothing else), the lane's part is a 32-bit byte offset
+// pos * row_bytes + col_bytes formed by one 24-bit multiply-add (the launcher checks that a
+// slice spans less than 4 GiB and that positions and row strides stay below 2^24).
+__device__ __forceinline__ uint4 load16(const char* base, int pos, unsigned row_bytes, unsigned col_bytes)
 {
-    return *reinterpret_cast<const uint4*>(base + (long long)pos * s_t);
+    const unsigned off = __umul24((unsigned)pos, row_bytes) + col_bytes;
+    return *reinterpret_cast<const uint4*>(base + off);
 }
-__device__ __forceinline__ Rows<2> load_rows(const uint16_t* base, Pos<2> p, long long s_t)
+__device__ __forceinline__ Rows<2> load_rows(const char* base, Pos<2> p, unsigned rb, unsigned cb)
 {
-    return Rows<2>{load16(base, p.p0, s_t), load16(base, p.p1, s_t)};
+    return Rows<2>{load16(base, p.p0, rb, cb), load16(base, p.p1, rb, cb)};
 }
-__device__ __forceinline__ Rows<4> load_rows(const uint16_t* base, Pos<4> p, long long s_t)
+__device__ __forceinline__ Rows<4> load_rows(const char* base, Pos<4> p, unsigned rb, unsigned cb)
 {
-    return Rows<4>{load16(base, p.p0, s_t), load16(base, p.p1, s_t), load16(base, p.p2, s_t),
-                   load16(base, p.p3, s_t)};
+    return Rows<4>{load16(base, p.p0, rb, cb), load16(base, p.p1, rb, cb), load16(base, p.p2, rb, cb),
+                   load16(base, p.p3, rb, cb)};
 }
+// Two floats rounded to bf16 and packed into one register (v_cvt_pk_bf16_f32), and the sum of
+// such a pair added to `acc` (v_dot2_f32_bf16 against (1, 1)).  The words are handled as plain
+// unsigned values and only the assembled operand is reinterpreted as eight bf16 values:
+// extracting words from a bf16 vector after element-wise stores made this compiler read the
+// first word four times.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ unsigned pack_bf16x2(float a, float b)
+{
+    const f32x2 v = {a, b};
+    return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
+}
+__device__ __forceinline__ float add_bf16x2(unsigned w, float acc)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w),
+                                           __builtin_bit_cast(bf16x2, 0x3f803f80u), acc, false);
+}
+
 __device__ __forceinline__ void store_rows(Rows<2> r, uint16_t* dst, int step)
 {
     *reinterpret_cast<uint4*>(dst) = r.r0;
@@ -113,16 +144,23 @@ __device__ __forceinline__ void store_rows(Rows<4> r, uint16_t* dst, int step)
     *reinterpret_cast<uint4*>(dst + 3 * step) = r.r3;
 }
 
-template <int U>
-__global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
-    Dims d, float scale_log2, int n_qt, int cu_per_xcd, const uint16_t* __restrict__ Q,
+// NW: waves per workgroup, each owning 32 queries of a work item of 32 NW queries.  NW = 8: one
+// workgroup per CU; NW = 4: two independent workgroups per CU (two waves per SIMD either way,
+// 256 registers each), so that one workgroup's start-up, epilogue and diagonal tiles overlap
+// with the other's tile loop.  DEPTH: register sets a tile passes through on its way from
+// global memory to LDS, i.e. how many iterations ahead of its LDS write a tile is requested.
+template <int NW, int DEPTH>
+__global__ __launch_bounds__(64 * NW, 2) void attend_bf16_kernel(
+    Dims d, float scale_log2, int n_qt, int n_xcd, const uint16_t* __restrict__ Q,
     const uint16_t* __restrict__ K, const uint16_t* __restrict__ V,
     const int32_t* __restrict__ kept_idx, uint16_t* __restrict__ O,
     const int32_t* __restrict__ counts, long long idx_stride)
 {
-    constexpr int NT = 512 / U;    // threads
+    constexpr int U = 1;           // 32-query sub-tiles per wave
+    constexpr int NT = 64 * NW;    // threads
     constexpr int CH = 1024 / NT;  // 16-byte chunks per thread per tensor per tile
     constexpr int WQ = 32 * U;     // queries per wave
+    constexpr int kBM = WQ * NW;   // kept queries per work item
     __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kKTile + 2 * kVTile];
     uint16_t* const k_lds = smem;               // 2 stages of K
     uint16_t* const v_lds = smem + 2 * kKTile;  // 2 stages of V
@@ -135,17 +173,19 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
     // Persistent workgroups, one per CU, with a static schedule.  (Left to the hardware
     // dispatcher, one workgroup per query tile, CUs sit idle for many microseconds whenever a
     // workgroup ends: it hands out workgroups in order, and the durations of causal query tiles
-    // differ by a factor of n_qt.)  The (batch, head) groups are split into eight contiguous
-    // runs, one per XCD, so an XCD's L2 holds the K and V of the few groups it is working on.
+    // differ by a factor of n_qt.)  The (batch, head) groups are split into n_xcd contiguous
+    // runs, one per XCD (the count is the device's, read by the host), so an XCD's L2 holds the
+    // K and V of the few groups it is working on.  Correctness does not depend on where a
+    // workgroup really runs, only the L2 hit rate does.
     const int n_groups = d.B * d.Hq;
-    // Static schedule: workgroup j of XCD x (x = id % 8, as the dispatcher deals them) walks
+    // Static schedule: workgroup j of XCD x (x = id % n_xcd, as the dispatcher deals them) walks
     // entries j, j + W, ... of the XCD's list of (group, pair of query tiles); a pair joins
     // query tile p with n_qt - 1 - p, so every entry is the same amount of causal work, and the
     // workgroups that share a group start on it together and stream the same K / V tiles.
-    const int x = blockIdx.x & 7, j = blockIdx.x >> 3;
-    const int nwx = (gridDim.x + 7 - x) >> 3;  // workgroups whose id % 8 is x
-    const int g_lo = x * n_groups / 8;
-    const int ng = (x + 1) * n_groups / 8 - g_lo;
+    const int x = blockIdx.x % n_xcd, j = blockIdx.x / n_xcd;
+    const int nwx = (gridDim.x + n_xcd - 1 - x) / n_xcd;  // workgroups whose id % n_xcd is x
+    const int g_lo = x * n_groups / n_xcd;
+    const int ng = (x + 1) * n_groups / n_xcd - g_lo;
     const int n_pairs = (n_qt + 1) >> 1;
     const int n_entries = ng * n_pairs;
 
@@ -200,10 +240,10 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
 
     const int32_t* idx = kept_idx + (long long)b * idx_stride;
     const uint16_t* Qb = Q + (long long)b * d.qs[0] + (long long)hq * d.qs[1];
-    const uint16_t* Kb = K + (long long)b * d.kvs[0] + (long long)hk * d.kvs[1];
-    const uint16_t* Vb = V + (long long)b * d.kvs[0] + (long long)hk * d.kvs[1];
+    const char* Kb = reinterpret_cast<const char*>(K + (long long)b * d.kvs[0] + (long long)hk * d.kvs[1]);
+    const char* Vb = reinterpret_cast<const char*>(V + (long long)b * d.kvs[0] + (long long)hk * d.kvs[1]);
     uint16_t* Ob = O + (long long)b * d.os[0] + (long long)hq * d.os[1];
-    const long long s_t = d.kvs[2];
+    const unsigned kv_row_bytes = (unsigned)d.kvs[2] * 2u;
 
     const int col = lane & 31, hh = lane >> 5;
 
@@ -231,7 +271,7 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
     Rows<CH> kreg_a, vreg_a, kreg_b, vreg_b;
     Pos<CH> pos_k, pos_v, pos_n;
 #define TF_LOAD_IDX(P, J0) P = load_pos(idx, (J0) + row0, RS, m_last, (Pos<CH>*)nullptr)
-#define TF_LOAD_ROWS(R, BASE, P) R = load_rows((BASE) + col0, P, s_t)
+#define TF_LOAD_ROWS(R, BASE, P) R = load_rows(BASE, P, kv_row_bytes, 2u * col0)
 #define TF_STORE_ROWS(R, STAGE, STRIDE) store_rows(R, (STAGE) + row0 * (STRIDE) + col0, RS * (STRIDE))
 #define TF_COPY_POS(DST, SRC) DST = SRC
 
@@ -241,14 +281,15 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
     for (int u = 0; u < U; ++u) qpos[u] = idx[lim[u]];
     Pos<CH> pos_0, pos_1;
     {
-        // (opaque copy of the row number: these four index sets do not depend on the item, and
+        // (opaque copy of the row number: these index sets do not depend on the item, and
         // would otherwise be kept in registers, or spilled, across the whole item loop)
         int row0p = row0;
         asm volatile("" : "+v"(row0p));
         pos_0 = load_pos(idx, row0p, RS, m_last, (Pos<CH>*)nullptr);
         pos_1 = load_pos(idx, kBN + row0p, RS, m_last, (Pos<CH>*)nullptr);
-        pos_v = load_pos(idx, 2 * kBN + row0p, RS, m_last, (Pos<CH>*)nullptr);
-        pos_k = load_pos(idx, 3 * kBN + row0p, RS, m_last, (Pos<CH>*)nullptr);
+        // rows of the tiles iteration 0 requests: V(DEPTH) and K(DEPTH + 1)
+        pos_v = load_pos(idx, DEPTH * kBN + row0p, RS, m_last, (Pos<CH>*)nullptr);
+        pos_k = load_pos(idx, (DEPTH + 1) * kBN + row0p, RS, m_last, (Pos<CH>*)nullptr);
     }
     // Q fragments (B operand of S^T = K Q^T): for sub-tile u, lane (col, hh) holds, for
     // k-step s, the 8 elements 16 s + 8 hh .. +7 of query row iw + 32 u + col.
@@ -263,11 +304,11 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
     TF_LOAD_ROWS(kreg_a, Kb, pos_0);  // K(0)
     TF_LOAD_ROWS(vreg_a, Vb, pos_0);  // V(0)
     TF_LOAD_ROWS(kreg_b, Kb, pos_1);  // K(1)
-    TF_LOAD_ROWS(vreg_b, Vb, pos_1);  // V(1), stays in registers until iteration 0 ends
+    if constexpr (DEPTH == 2) TF_LOAD_ROWS(vreg_b, Vb, pos_1);  // V(1), stays in registers until iteration 0 ends
     TF_STORE_ROWS(kreg_a, k_lds, kKStr);
     TF_STORE_ROWS(vreg_a, v_lds, kVStr);
     TF_STORE_ROWS(kreg_b, k_lds + kKTile, kKStr);
-    TF_LOAD_ROWS(kreg_a, Kb, pos_v);  // K(2), stays in flight
+    if constexpr (DEPTH == 2) TF_LOAD_ROWS(kreg_a, Kb, pos_v);  // K(2), stays in flight
     __syncthreads();
 
     // LDS offsets of this lane's operand fragments inside a K / V stage
@@ -282,11 +323,13 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
 #pragma unroll
             for (int v = 0; v < 16; ++v) oacc[u][dt][v] = 0.f;
     float m_run[U];  // running max of the RAW scores (may lag, see kMaxSlack)
-    float l_run[U];  // this lane's share of the softmax denominators
+    float l_run[U];  // this lane's share of the softmax denominators, in two independent
+    float l_alt[U];  // chains (even / odd pairs of keys)
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         m_run[u] = kMasked;
         l_run[u] = 0.f;
+        l_alt[u] = 0.f;
     }
 
     bf16x8 kf[8];           // K fragments of the 32 keys whose scores are computed next
@@ -328,9 +371,14 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
             for (int v = 0; v < 16; ++v)
                 if (t + (8 * (v >> 2) + (v & 3)) > 0) sacc[v] = kMasked;
         }
-        float mx = fmaxf(sacc[0], sacc[1]);
+        // two chains of three-operand maxima
+        float mx = fmaxf(sacc[0], sacc[1]), my = fmaxf(sacc[2], sacc[3]);
 #pragma unroll
-        for (int v = 2; v < 16; v += 2) mx = fmaxf(mx, fmaxf(sacc[v], sacc[v + 1]));
+        for (int v = 4; v < 16; v += 4) {
+            mx = fmaxf(fmaxf(mx, sacc[v]), sacc[v + 1]);
+            my = fmaxf(fmaxf(my, sacc[v + 2]), sacc[v + 3]);
+        }
+        mx = fmaxf(mx, my);
         // the other half of this query's keys sits 32 lanes away: swap halves in the VALU
         const FloatPair sw = swap32(mx, mx);
         return fmaxf(sw.first, sw.second);
@@ -344,6 +392,7 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
             const float corr = __builtin_amdgcn_exp2f((m_run[u] - m_new) * scale_log2);
             m_run[u] = m_new;
             l_run[u] *= corr;
+            l_alt[u] *= corr;
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -362,13 +411,20 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
         TF_QK(S_NXT);                                                                          \
         _Pragma("unroll") for (int u = 0; u < U; ++u) {                                        \
             const float mc = m_run[u] * scale_log2;                                            \
-            float ps_[4] = {0.f, 0.f, 0.f, 0.f};                                               \
-            _Pragma("unroll") for (int v = 0; v < 16; ++v) {                                   \
-                const float p = __builtin_amdgcn_exp2f(fmaf(S_CUR[u][v], scale_log2, -mc));    \
-                ps_[v & 3] += p;                                                               \
-                pf[u][v >> 3][v & 7] = (__bf16)p;                                              \
+            float p_[16];                                                                      \
+            _Pragma("unroll") for (int v = 0; v < 16; ++v)                                     \
+                p_[v] = __builtin_amdgcn_exp2f(fmaf(S_CUR[u][v], scale_log2, -mc));            \
+            /* the denominator sums the weights AS ROUNDED for the matrix product, so every */ \
+            /* output row is an exact convex combination of value rows                      */ \
+            _Pragma("unroll") for (int ks2 = 0; ks2 < 2; ++ks2) {                              \
+                u32x4 w_;                                                                      \
+                _Pragma("unroll") for (int i = 0; i < 4; ++i) {                                \
+                    w_[i] = pack_bf16x2(p_[8 * ks2 + 2 * i], p_[8 * ks2 + 2 * i + 1]);         \
+                    if (i & 1) l_alt[u] = add_bf16x2(w_[i], l_alt[u]);                         \
+                    else l_run[u] = add_bf16x2(w_[i], l_run[u]);                               \
+                }                                                                              \
+                pf[u][ks2] = __builtin_bit_cast(bf16x8, w_);                                   \
             }                                                                                  \
-            l_run[u] += (ps_[0] + ps_[1]) + (ps_[2] + ps_[3]);                                 \
         }                                                                                      \
         /* block 2 */                                                                          \
         read_kf(KS_NEXT);                                                                      \
@@ -394,15 +450,16 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
     }
     __syncthreads();  // K(0) is fully in registers before iteration 0 may overwrite its stage
 
-    // Iteration kt: issue the loads of K(kt + 3) and V(kt + 2) into register set LD, do the two
-    // steps of tile kt, then write set ST (K(kt + 2), V(kt + 1), issued one iteration earlier)
-    // into the stages that K(kt) and V(kt - 1) have left.  Index loads go first so that
-    // waiting for them leaves the row loads in flight.
+    // Iteration kt: issue the loads of K(kt + 1 + DEPTH) and V(kt + DEPTH) into register set LD,
+    // do the two steps of tile kt, then write set ST (K(kt + 2), V(kt + 1); with DEPTH = 2 issued
+    // one iteration earlier into the other set, with DEPTH = 1 the loads just issued) into the
+    // stages that K(kt) and V(kt - 1) have left.  Index loads go first so that waiting for them
+    // leaves the row loads in flight.
 #define TF_ITERATION(KT, LD_K, LD_V, ST_K, ST_V)                                                \
     do {                                                                                       \
         const int cur = (KT) & 1;                                                              \
         const int j0 = (KT) * kBN;                                                             \
-        TF_LOAD_IDX(pos_n, j0 + 4 * kBN);                                                      \
+        TF_LOAD_IDX(pos_n, j0 + (2 + DEPTH) * kBN);                                            \
         TF_LOAD_ROWS(LD_K, Kb, pos_k);                                                         \
         TF_LOAD_ROWS(LD_V, Vb, pos_v);                                                         \
         TF_COPY_POS(pos_v, pos_k);                                                             \
@@ -420,11 +477,15 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
         __syncthreads();                                                                       \
     } while (0)
 
-    // after the prologue: kreg_a = K(2) is in flight, vreg_b = V(1) is loaded; pos_k / pos_v
-    // hold the rows of tile 3 / tile 2
+    // after the prologue, DEPTH = 2: kreg_a = K(2) is in flight, vreg_b = V(1) is loaded
     for (int kt = 0; kt < n_kt; kt += 2) {
-        TF_ITERATION(kt, kreg_b, vreg_a, kreg_a, vreg_b);
-        if (kt + 1 < n_kt) TF_ITERATION(kt + 1, kreg_a, vreg_b, kreg_b, vreg_a);
+        if constexpr (DEPTH == 2) {
+            TF_ITERATION(kt, kreg_b, vreg_a, kreg_a, vreg_b);
+            if (kt + 1 < n_kt) TF_ITERATION(kt + 1, kreg_a, vreg_b, kreg_b, vreg_a);
+        } else {
+            TF_ITERATION(kt, kreg_a, vreg_a, kreg_a, vreg_a);
+            if (kt + 1 < n_kt) TF_ITERATION(kt + 1, kreg_a, vreg_a, kreg_a, vreg_a);
+        }
     }
 #undef TF_ITERATION
 #undef TF_STEP
@@ -450,7 +511,8 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
     uint16_t* os = smem + wave * (WQ * kOStr);  // [WQ queries][kOStr]
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const float l_tot = l_run[u] + __shfl_xor(l_run[u], 32);
+        const float l_mine = l_run[u] + l_alt[u];
+        const float l_tot = l_mine + __shfl_xor(l_mine, 32);
         const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
@@ -506,17 +568,23 @@ __global__ __launch_bounds__(512 / U) void attend_bf16_kernel(
 }  // namespace
 
 hipError_t launch_attend_bf16(const Dims& d, float scale, const void* Q, const void* K,
-                              const void* V, const int32_t* kept_idx, void* O, int n_cu,
+                              const void* V, const int32_t* kept_idx, void* O, int n_cu, int n_xcd,
                               const int32_t* counts, long long idx_stride, hipStream_t s)
 {
-    constexpr int U = 1;
+    // the tile gathers address a row as a 32-bit byte offset from its (batch, head) slice
+    if (d.n > (1 << 24) || d.kvs[2] * 2 >= (1 << 24) || (long long)d.n * d.kvs[2] * 2 >= (1ll << 32))
+        return hipErrorInvalidValue;
+    n_xcd = std::max(n_xcd, 1);
     // with per-row counts d.m is the bound (the longest possible row)
+    constexpr int NW = TF_ATTEND_NW, DEPTH = TF_ATTEND_DEPTH;
+    constexpr int kBM = 32 * NW, wg_per_cu = 8 / NW;
     const int n_qt = (d.m + kBM - 1) / kBM;
     const long long items = (long long)d.B * d.Hq * n_qt;
-    // at least eight workgroups: every residue of id % 8 owns a share of the groups
-    const int grid = (int)std::max<long long>(8, std::min<long long>(items, std::max(n_cu, 1)));
-    attend_bf16_kernel<U><<<dim3(grid), dim3(512 / U), 0, s>>>(
-        d, scale * 1.44269504088896340736f, n_qt, std::max(n_cu / 8, 1), (const uint16_t*)Q,
+    // persistent workgroups: as many as are resident at once; at least one per XCD, so that every
+    // residue of id % n_xcd owns a share of the groups
+    const int grid = (int)std::max<long long>(n_xcd, std::min<long long>(items, (long long)wg_per_cu * std::max(n_cu, 1)));
+    attend_bf16_kernel<NW, DEPTH><<<dim3(grid), dim3(64 * NW), 0, s>>>(
+        d, scale * 1.44269504088896340736f, n_qt, n_xcd, (const uint16_t*)Q,
         (const uint16_t*)K, (const uint16_t*)V, kept_idx, (uint16_t*)O, counts,
         counts ? idx_stride : (long long)d.m);
     return hipGetLastError();

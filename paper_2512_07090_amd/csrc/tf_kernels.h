@@ -67,9 +67,10 @@ hipError_t launch_attend_f32(const Dims& d, float scale, const float* Q, const f
                              const float* V, const int32_t* kept_idx, float* O,
                              const int32_t* counts, long long idx_stride, hipStream_t s);
 // also writes the zero rows of filtered positions (kept_idx strictly ascending).  n_cu: compute
-// units of the device (one persistent workgroup each).
+// units of the device (one persistent workgroup each); n_xcd: its accelerator dies (each with an
+// L2 of its own).  hipErrorInvalidValue if a (batch, head) slice of K / V spans 4 GiB or more.
 hipError_t launch_attend_bf16(const Dims& d, float scale, const void* Q, const void* K,
-                              const void* V, const int32_t* kept_idx, void* O, int n_cu,
+                              const void* V, const int32_t* kept_idx, void* O, int n_cu, int n_xcd,
                               const int32_t* counts, long long idx_stride, hipStream_t s);
 
 // ---- per-token (decoding) form ----------------------------------------------------------------

@@ -12,7 +12,8 @@
 
 struct tf_ctx {
     int device;
-    int n_cu;  // compute units of the device
+    int n_cu;   // compute units of the device
+    int n_xcd;  // accelerator dies (each has its own L2)
     char err[256];
     int timing_on;
     int timing_calls;
@@ -81,6 +82,11 @@ tf_status check_shape(const tf_params* p, const char** why)
     if (p->head_dim != tf::kHeadDim) { *why = "only head_dim 128 is supported"; return TF_ERR_UNSUPPORTED; }
     if (p->n_kv_heads > kMaxKvHeads) { *why = "more than 128 KV heads is not supported"; return TF_ERR_UNSUPPORTED; }
     if ((int64_t)p->batch * p->seq > (int64_t)1 << 30) { *why = "batch * seq too large"; return TF_ERR_UNSUPPORTED; }
+    if (p->dtype == TF_BF16 && (p->seq > (1 << 24) || p->kv_stride[2] * 2 >= (1 << 24) ||
+                                (int64_t)p->seq * p->kv_stride[2] * 2 >= ((int64_t)1 << 32))) {
+        *why = "a (batch, head) slice of K / V must span less than 4 GiB (bf16 attention addresses rows by 32-bit offsets)";
+        return TF_ERR_UNSUPPORTED;
+    }
     // batch rows and query heads index the second and third grid dimension of some launches
     if (p->batch > 65535 || p->n_q_heads > 65535) {
         *why = "batch and n_q_heads above 65535 are not supported"; return TF_ERR_UNSUPPORTED;
@@ -164,7 +170,7 @@ tf_status run_attend(tf_ctx* ctx, const tf_params* p, const tf::Dims& d, const v
     }
     // the bf16 kernel writes the zero rows itself
     mark(ctx, slot, TF_STAGE_ATTEND, s);
-    return dev(ctx, tf::launch_attend_bf16(d, scale, Q, K, V, kept_idx, O, ctx->n_cu, counts, p->seq, s),
+    return dev(ctx, tf::launch_attend_bf16(d, scale, Q, K, V, kept_idx, O, ctx->n_cu, ctx->n_xcd, counts, p->seq, s),
                "bf16 attention launch");
 }
 
@@ -271,6 +277,8 @@ tf_status tf_create(tf_ctx** out, int device)
         delete c;
         return TF_ERR_DEVICE;
     }
+    if (hipDeviceGetAttribute(&c->n_xcd, hipDeviceAttributeNumberOfXccs, device) != hipSuccess || c->n_xcd < 1)
+        c->n_xcd = 1;  // unknown: one run of groups; only cache locality depends on it
     *out = c;
     return TF_OK;
 }
@@ -286,9 +294,9 @@ void tf_destroy(tf_ctx* ctx)
     delete ctx;
 }
 
-const char* tf_status_string(tf_status s)
+const char* tf_status_string(int status)
 {
-    switch (s) {
+    switch (status) {
         case TF_OK: return "ok";
         case TF_ERR_INVALID_ARG: return "invalid argument";
         case TF_ERR_UNSUPPORTED: return "unsupported configuration";
