@@ -10,6 +10,7 @@
  *
  * Groups of entry points
  *   - batched, exact count:  tf_score, tf_select, tf_attend, tf_filtered_attention
+ *     (tf_filtered_attention_static: the same without a workspace argument)
  *   - batched, online threshold (Section 3.3, Eq. 4):  tf_select_online, tf_attend_ragged,
  *     tf_filtered_attention_online
  *   - tail-focused layer schedule (Eq. 3):  tf_tail_schedule, tf_filtered_attention_layers
@@ -207,6 +208,22 @@ tf_status tf_filtered_attention_online(tf_ctx *ctx, const tf_params *p, float et
 tf_status tf_filtered_attention(tf_ctx *ctx, const tf_params *p, const void *Q, const void *K,
                                 const void *V, uint8_t *keep, int32_t *kept_idx, float *fused,
                                 float *tau, void *O, void *ws, size_t ws_bytes, void *stream);
+
+/* tf_filtered_attention for callers that cannot allocate device memory or bring a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, outputs, kernels and results as tf_filtered_attention, without `ws`: the
+ * intermediates (per-head cosines, segment totals) live in a fixed array of
+ * TF_STATIC_SCRATCH_BYTES of device memory inside the library (each GPU the library runs on
+ * holds it until the process ends).  The call allocates and frees nothing.  A shape for which
+ * tf_workspace_bytes(p) exceeds TF_STATIC_SCRATCH_BYTES is rejected with TF_ERR_UNSUPPORTED
+ * before anything is enqueued.  All calls on one GPU share the array: two calls that overlap in
+ * time on one GPU (different streams, different contexts or threads) race on it; calls that
+ * follow each other in one stream do not. */
+#define TF_STATIC_SCRATCH_BYTES (16u << 20)
+tf_status tf_filtered_attention_static(tf_ctx *ctx, const tf_params *p, const void *Q,
+                                       const void *K, const void *V, uint8_t *keep,
+                                       int32_t *kept_idx, float *fused, float *tau, void *O,
+                                       void *stream);
 
 /* Per-token form of the layer: Algorithm 1 called once per new token of every batch row
  * (anchor of Section 3.2 / Eq. 1, fusion of Eq. 2, warm-up of Section 3.2, threshold rule of

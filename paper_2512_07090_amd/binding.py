@@ -28,7 +28,9 @@ EXPORTS = ("tf_create", "tf_destroy", "tf_status_string", "tf_last_error", "tf_k
            "tf_stage_timing_enable", "tf_stage_timing_read", "tf_probe_hbm_read",
            "tf_probe_mfma_bf16", "tf_tail_schedule", "tf_filtered_attention_layers",
            "tf_select_online", "tf_attend_ragged", "tf_filtered_attention_online",
-           "tf_decode_workspace_bytes", "tf_decode_init", "tf_decode_step", "tf_decode_prefill")
+           "tf_decode_workspace_bytes", "tf_decode_init", "tf_decode_step", "tf_decode_prefill",
+           "tf_filtered_attention_static")
+TF_STATIC_SCRATCH_BYTES = 16 << 20
 
 
 class tf_params(ctypes.Structure):
@@ -85,6 +87,8 @@ def lib():
         L.tf_select.argtypes = [vp, pp, vp, vp, vp, vp, vp, sz, vp]
         L.tf_attend.argtypes = [vp, pp, vp, vp, vp, vp, i32, vp, vp, sz, vp]
         L.tf_filtered_attention.argtypes = [vp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.tf_filtered_attention_static.argtypes = [vp, pp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.tf_filtered_attention_static.restype = ctypes.c_int
         L.tf_stage_timing_enable.argtypes = [vp, ctypes.c_int]
         L.tf_stage_timing_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
         flt = ctypes.c_float
@@ -274,6 +278,11 @@ class Context:
             self._h, ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(keep), _ptr(kept_idx),
             _ptr(fused), _ptr(tau), _ptr(O), _ptr(ws),
             0 if ws is None else ws.numel() * ws.element_size(), _stream(stream)))
+
+    def tf_filtered_attention_static(self, p, Q, K, V, keep, kept_idx, fused, tau, O, stream=None):
+        self._check(lib().tf_filtered_attention_static(
+            self._h, ctypes.byref(p), _ptr(Q), _ptr(K), _ptr(V), _ptr(keep), _ptr(kept_idx),
+            _ptr(fused), _ptr(tau), _ptr(O), _stream(stream)))
 
     def tf_select_online(self, p, eta, tau0, fused, keep, kept_idx, count, tau, ws, stream=None):
         self._check(lib().tf_select_online(

@@ -10,10 +10,16 @@
 #include "../../include/tokfilt.h"
 #include "tf_kernels.h"
 
+// Scratch of tf_filtered_attention_static: a fixed array in device memory, one copy per GPU the
+// library is loaded on, held until the process ends.  In host code this name is only a handle
+// for hipGetSymbolAddress; the address kernels and copies use is the one kept in the context.
+static __device__ __align__(256) unsigned char scratch[TF_STATIC_SCRATCH_BYTES];
+
 struct tf_ctx {
     int device;
     int n_cu;   // compute units of the device
     int n_xcd;  // accelerator dies (each has its own L2)
+    void* static_scratch;  // device address of `scratch` on this context's GPU
     char err[256];
     int timing_on;
     int timing_calls;
@@ -279,6 +285,13 @@ tf_status tf_create(tf_ctx** out, int device)
     }
     if (hipDeviceGetAttribute(&c->n_xcd, hipDeviceAttributeNumberOfXccs, device) != hipSuccess || c->n_xcd < 1)
         c->n_xcd = 1;  // unknown: one run of groups; only cache locality depends on it
+    // every GPU holds its own copy of the static scratch array at its own address: ask for it
+    // with this context's device current
+    if (hipSetDevice(device) != hipSuccess ||
+        hipGetSymbolAddress(&c->static_scratch, HIP_SYMBOL(scratch)) != hipSuccess || !c->static_scratch) {
+        delete c;
+        return TF_ERR_DEVICE;
+    }
     *out = c;
     return TF_OK;
 }
@@ -550,6 +563,29 @@ tf_status tf_filtered_attention(tf_ctx* ctx, const tf_params* p, const void* Q, 
     if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O))
         return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V and O must be 16-byte aligned");
     return run_path(ctx, p, w, Q, K, V, keep, kept_idx, fused, tau, O, ws, (hipStream_t)stream);
+}
+
+tf_status tf_filtered_attention_static(tf_ctx* ctx, const tf_params* p, const void* Q,
+                                       const void* K, const void* V, uint8_t* keep,
+                                       int32_t* kept_idx, float* fused, float* tau, void* O,
+                                       void* stream)
+{
+    if (!ctx) return TF_ERR_INVALID_ARG;
+    const char* why;
+    const tf_status s = check_shape(p, &why);
+    if (s != TF_OK) return fail(ctx, s, "%s", why);
+    const Workspace w = carve(p);
+    if (w.total > (size_t)TF_STATIC_SCRATCH_BYTES)
+        return fail(ctx, TF_ERR_UNSUPPORTED,
+                    "this shape needs %zu bytes of scratch, the static scratch holds %zu: use "
+                    "tf_filtered_attention with a workspace", w.total, (size_t)TF_STATIC_SCRATCH_BYTES);
+    if (!Q || !K || !V || !O || !keep || !kept_idx || !fused)
+        return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V, O, keep, kept_idx and fused must not be NULL");
+    if (misaligned(Q) || misaligned(K) || misaligned(V) || misaligned(O))
+        return fail(ctx, TF_ERR_INVALID_ARG, "Q, K, V and O must be 16-byte aligned");
+    if (hipSetDevice(ctx->device) != hipSuccess) return fail(ctx, TF_ERR_DEVICE, "hipSetDevice(%d) failed", ctx->device);
+    // nothing in the scratch has to start at zero: every kernel of the path writes what it reads
+    return run_path(ctx, p, w, Q, K, V, keep, kept_idx, fused, tau, O, ctx->static_scratch, (hipStream_t)stream);
 }
 
 tf_status tf_tail_schedule(int32_t n_layers, double p_global, double tail_fraction,

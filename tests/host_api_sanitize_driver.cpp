@@ -33,6 +33,7 @@ int main() {
     // every device entry point refuses a NULL context before touching anything
     if (tf_score(NULL, &p, 0, 0, 0, 0, 0, 0, 0, 0) != TF_ERR_INVALID_ARG) ++bad;
     if (tf_filtered_attention(NULL, &p, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0) != TF_ERR_INVALID_ARG) ++bad;
+    if (tf_filtered_attention_static(NULL, &p, 0, 0, 0, 0, 0, 0, 0, 0, 0) != TF_ERR_INVALID_ARG) ++bad;
     printf("host api driver: %d failures\n", bad);
     return bad ? 1 : 0;
 }
