@@ -81,18 +81,38 @@ struct Row8<float> {
     }
 };
 
+// The 8 rows t_first .. t_first + 7 of a thread, columns col .. col + 7.  Every load is issued
+// whatever the row: rows at or past t_end re-read row t_end - 1 (t_end >= 1) and are zeroed by
+// clear_rows_past() once they are used, so that no load sits under a branch and the compiler
+// can count how many loads are still in flight when it waits for a tile.
 template <typename T>
 __device__ __forceinline__ void load_tile(Row8<T>* rows, const T* X, long long s_t, int t_first,
                                           int t_end, int col)
 {
 #pragma unroll
     for (int r = 0; r < kR; ++r) {
-        const int t = t_first + r;
-        if (t < t_end)
-            rows[r].load(X + (long long)t * s_t + col);
-        else
-            rows[r].zero();
+        const int t = min(t_first + r, t_end - 1);
+        rows[r].load(X + (long long)t * s_t + col);
     }
+}
+template <typename T>
+__device__ __forceinline__ void clear_rows_past(Row8<T>* rows, int t_first, int t_end)
+{
+#pragma unroll
+    for (int r = 0; r < kR; ++r)
+        if (t_first + r >= t_end) rows[r].zero();
+}
+
+// One score to global memory.  Written as an instruction of its own so that the compiler's wait
+// counting sees loads only: the hardware counts loads and stores in one counter and lets a store
+// overtake a load, and with a store possibly in flight the compiler waits for ALL outstanding
+// memory operations, the tiles just requested included.  Loads return in order among
+// themselves, so "at most k operations outstanding" still means that all but the newest k loads
+// have arrived, whether stores are among the outstanding ones or not; nothing in the kernel
+// reads a score back.
+__device__ __forceinline__ void store_score(float* p, float v)
+{
+    asm volatile("global_store_dword %0, %1, off" : : "v"(p), "v"(v) : "memory");
 }
 
 // Column totals of segments 0..nseg-2 of every chain.
@@ -113,6 +133,7 @@ __global__ __launch_bounds__(kThreads) void segment_totals_kernel(
     for (int t0 = t_begin; t0 < t_end; t0 += kTile) {
         Row8<T> rows[kR];
         load_tile(rows, X, s_t, t0 + rg * kR, t_end, 8 * l);
+        if (t0 + kTile > t_end) clear_rows_past(rows, t0 + rg * kR, t_end);
 #pragma unroll
         for (int r = 0; r < kR; ++r) {
             float x[8];
@@ -185,9 +206,10 @@ __global__ __launch_bounds__(kThreads) void scan_score_kernel(
     load_tile(buf1, X, s_t, t_begin + kTile + rg * kR, t_end, 8 * l);
 
     int parity = 0;
-    auto process = [&](const Row8<T>* rows, int t0, bool first_tile) {
+    auto process = [&](Row8<T>* rows, int t0, bool first_tile) {
         float x[kR][8];
         float tot[8];
+        if (t0 + kTile > t_end) clear_rows_past(rows, t0 + rg * kR, t_end);  // uniform branch
 #pragma unroll
         for (int r = 0; r < kR; ++r) rows[r].unpack(x[r]);
 #pragma unroll
@@ -220,32 +242,25 @@ __global__ __launch_bounds__(kThreads) void scan_score_kernel(
         __syncthreads();
         float A[8], all[8];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) { A[c] = carry[c]; all[c] = EMA ? carry[c] : 0.f; }
+        for (int c = 0; c < 8; ++c) { A[c] = 0.f; all[c] = carry[c]; }  // `all` runs on from the carry
+        // (`wave` is uniform: what is "before this wave" is decided by scalar branches; written
+        // as a per-lane condition it became 32 selects a tile)
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             const float4* src = reinterpret_cast<const float4*>(&wtot[parity][w][8 * l]);
             const float4 a = src[0], b = src[1];
             const float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+            if (w == wave) {
 #pragma unroll
-            for (int c = 0; c < 8; ++c) {
-                if (EMA) {
-                    all[c] = fmaf(g32, all[c], v[c]);
-                    if (w < wave) A[c] = fmaf(g32, A[c], v[c]);
-                } else {
-                    all[c] += v[c];
-                    if (w < wave) A[c] += v[c];
-                }
+                for (int c = 0; c < 8; ++c) A[c] = all[c];   // the waves before this one
             }
+#pragma unroll
+            for (int c = 0; c < 8; ++c) all[c] = EMA ? fmaf(g32, all[c], v[c]) : all[c] + v[c];
         }
 #pragma unroll
         for (int c = 0; c < 8; ++c) {
-            if (EMA) {
-                carry[c] = all[c];
-                A[c] = fmaf(g_rgw, A[c], excl[c]);
-            } else {
-                carry[c] += all[c];
-                A[c] += excl[c];
-            }
+            carry[c] = all[c];
+            A[c] = EMA ? fmaf(g_rgw, A[c], excl[c]) : A[c] + excl[c];
         }
         parity ^= 1;
 
@@ -300,7 +315,7 @@ __global__ __launch_bounds__(kThreads) void scan_score_kernel(
                 const float den = fmaxf(sqrtf(aa) * sqrtf(my_xx) * inv_t, 1e-8f);
                 float cs = (num * inv_t) / den;
                 cs = fminf(1.f, fmaxf(-1.f, cs));
-                sim[t] = cs;
+                store_score(sim + t, cs);
             }
         }
     };

@@ -214,6 +214,35 @@ def test_score_parity_anchor_including_the_token(ctx, shape):
     assert np.all(np.abs(buf.sim_k.cpu().numpy()[:, :, 0] - 1) <= 1e-6)    # a token against itself
 
 
+@pytest.mark.parametrize("shape", [
+    # (dtype, B, Hq, Hkv, n): one tile, a ragged second tile, many tiles with few chains (many
+    # segments per chain), many chains with few tiles
+    ("bf16", 1, 2, 2, 100), ("f32", 2, 4, 2, 300), ("bf16", 2, 8, 2, 1000), ("f32", 1, 2, 1, 2049),
+    ("bf16", 1, 1, 1, 9000), ("bf16", 1, 32, 8, 4133), ("bf16", 3, 40, 40, 700),
+])
+def test_score_parity_exact_mean_on_a_stale_workspace(ctx, shape):
+    """Exact-mean scoring, either reading of the anchor, on a workspace full of 0xFF bytes."""
+    dt, Bn, Hq, Hkv, n = shape
+    _say("score, stale workspace %s" % (shape,))
+    q, k, v, _ = synth.make_random_qkv(Bn, Hq, Hkv, n, 128, dtype=dt, seed=900 + n)
+    kd, vd = k.cuda(), v.cuda()
+    for inclusive in (False, True):
+        p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.5, anchor_inclusive=inclusive)
+        buf = B.Buffers(p, "cuda:0", with_sims=True)
+        buf.ws.fill_(0xFF)
+        ck, cv = oracle.anchor_cosine(k, inclusive=inclusive), oracle.anchor_cosine(v, inclusive=inclusive)
+        for mode in (B.TF_FUSE_EQ2, B.TF_FUSE_KEY_ONLY):
+            p.fusion = mode
+            buf.sim_k.fill_(7.0)
+            buf.sim_v.fill_(7.0)
+            ctx.tf_score(p, kd, vd, buf.fused, buf.sim_k, buf.sim_v, buf.ws)
+            torch.cuda.synchronize()
+            assert_scores_close(buf.sim_k.cpu().numpy(), ck, "sim_k")
+            if mode == B.TF_FUSE_EQ2:
+                assert_scores_close(buf.sim_v.cpu().numpy(), cv, "sim_v")
+            assert_scores_close(buf.fused.cpu().numpy(), oracle.fuse(ck, cv, mode), "fused mode %d" % mode)
+
+
 def test_whole_path_incremental_anchor(ctx):
     _say("whole path ema")
     w = synth.scaled(synth.workload(1), batch=2, seq=1800, n_q_heads=8, n_kv_heads=8)
@@ -552,12 +581,19 @@ def test_probes_report_plausible_rates(ctx):
 
 # ------------------------------------------------------------------ stream capture
 
-def test_whole_path_replays_from_a_captured_graph(ctx):
+@pytest.mark.parametrize("wl", [
+    # fp32 and bf16, the latter also with grouped heads
+    dict(base=0, batch=2, seq=1500, n_q_heads=8, n_kv_heads=8),
+    dict(base=1, batch=2, seq=1500, n_q_heads=8, n_kv_heads=8),
+    dict(base=3, batch=1, seq=3000, n_q_heads=8, n_kv_heads=2),
+])
+def test_whole_path_replays_from_a_captured_graph(ctx, wl):
     """The whole-path call allocates nothing and never synchronises, so it can be captured into
     a HIP graph.  Every replay (with eager work and synchronisation in between) must reproduce
     the eager outputs bit for bit."""
-    _say("graph replay")
-    w = synth.scaled(synth.workload(1), batch=2, seq=1500, n_q_heads=8, n_kv_heads=8)
+    _say("graph replay %s" % (wl,))
+    wl = dict(wl)
+    w = synth.scaled(synth.workload(wl.pop("base")), **wl)
     q, k, v, _ = synth.make_qkv(w)
     qd, kd, vd = q.cuda(), k.cuda(), v.cuda()
     p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.5)
