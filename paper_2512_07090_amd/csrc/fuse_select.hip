@@ -247,9 +247,23 @@ __global__ __launch_bounds__(kSelThreads) void select_compact_kernel(
             const unsigned himask = pass == 0 ? 0u : (0xffffffffu << (shift + 8));
             if (tid < 256) hist[tid] = 0;
             __syncthreads();
+            // a thread's consecutive tokens that fall into the same bin share one atomic: scores
+            // are cosines, so in the first passes nearly all of them do, and colliding atomics
+            // are what this loop costs
+            int run_bin = -1, run_len = 0;
 #pragma unroll
-            for (int i = 0; i < IPT; ++i)
-                if (cand[i] && (key[i] & himask) == prefix) atomicAdd(&hist[(key[i] >> shift) & 255u], 1);
+            for (int i = 0; i < IPT; ++i) {
+                if (cand[i] && (key[i] & himask) == prefix) {
+                    const int bin = (int)((key[i] >> shift) & 255u);
+                    if (bin != run_bin) {
+                        if (run_len) atomicAdd(&hist[run_bin], run_len);
+                        run_bin = bin;
+                        run_len = 0;
+                    }
+                    ++run_len;
+                }
+            }
+            if (run_len) atomicAdd(&hist[run_bin], run_len);
             __syncthreads();
             const int cnt = tid < 256 ? hist[tid] : 0;
             int total;
