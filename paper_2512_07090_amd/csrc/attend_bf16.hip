@@ -195,10 +195,23 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_bf16_kernel(
     // which only has zero rows to write), so that, as in the uniform case, workgroups with
     // neighbouring ids work on the same group.  (rb, row_e0): the batch row the current entry
     // lies in and the first entry of that row; entries only move forward.
+    //
+    // Uniform rows, last round: when the entries do not fill a whole number of rounds and the
+    // rest (L entries) is at most half a round, those L entries are not dealt as pairs, which
+    // would keep every other workgroup idle for a whole pair: they are the MIDDLE pairs of the
+    // last L groups (the pair whose two tiles are closest in work), taken out of the list of
+    // whole rounds, and their 2 L tiles go to workgroups 0 .. 2 L - 1, one tile each (two
+    // neighbours share a group).  The last round then lasts one middle tile instead of a pair.
+    const int full_rounds = n_entries / nwx;
+    const int rest = n_entries - full_rounds * nwx;
+    const bool split_rest = !counts && rest > 0 && 2 * rest <= nwx && rest <= ng && n_pairs >= 2 && (n_qt & 1) == 0;
+    const int n_main = split_rest ? n_entries - rest : n_entries;  // entries dealt as pairs
+    const int whole_groups = split_rest ? ng - rest : ng;          // groups that keep all their pairs
     int rb = g_lo / d.Hq, row_e0 = 0;
     for (int it = 0;; ++it) {
     const int e = j + (it >> 1) * nwx;
     int pr, bh, m, nq;
+    bool single = false;  // this entry is one tile of a split middle pair
     if (counts) {
         int P = 1;
         bool done = false;
@@ -217,11 +230,24 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_bf16_kernel(
         bh = max(g_lo, rb * d.Hq) + el / P;
         pr = el % P;
     } else {
-        if (e >= n_entries) break;
-        pr = e % n_pairs;
-        bh = g_lo + e / n_pairs;
         m = d.m;
         nq = n_qt;
+        if (e < n_main) {
+            const int e_whole = whole_groups * n_pairs;  // entries of the groups with all pairs
+            if (e < e_whole) {
+                pr = e % n_pairs;
+                bh = g_lo + e / n_pairs;
+            } else {  // the last groups have given their middle pair away
+                pr = (e - e_whole) % (n_pairs - 1);
+                bh = g_lo + whole_groups + (e - e_whole) / (n_pairs - 1);
+            }
+        } else {
+            // past the whole rounds: one tile of a middle pair, or nothing
+            if (!split_rest || (it >> 1) != full_rounds || (it & 1) || j >= 2 * rest) break;
+            single = true;
+            pr = n_pairs - 1;
+            bh = g_lo + whole_groups + (j >> 1);
+        }
     }
     const int b = bh / d.Hq, hq = bh % d.Hq;
     const int hk = hq / (d.Hq / d.Hkv);
@@ -235,8 +261,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_bf16_kernel(
         continue;
     }
     if (pr >= (nq + 1) >> 1) continue;
-    const int qt = (it & 1) ? pr : nq - 1 - pr;
-    if ((it & 1) && pr == nq - 1 - pr) continue;  // the middle tile of an odd count is alone
+    const int qt = single ? ((j & 1) ? pr : nq - 1 - pr) : ((it & 1) ? pr : nq - 1 - pr);
+    if (!single && (it & 1) && pr == nq - 1 - pr) continue;  // the middle tile of an odd count is alone
 
     const int32_t* idx = kept_idx + (long long)b * idx_stride;
     const uint16_t* Qb = Q + (long long)b * d.qs[0] + (long long)hq * d.qs[1];

@@ -432,6 +432,22 @@ def test_whole_path_reduced_bf16_workloads(ctx, wl):
         check_whole_path(ctx, q, k, v, r)
 
 
+@pytest.mark.parametrize("wl", [
+    # 160 (batch, head) groups: on eight XCDs of 32 workgroups each, an XCD's 20 groups x 2 pairs
+    # leave 8 pairs after the whole rounds, which the schedule deals as single middle tiles (the
+    # full-size workload 3 leaves 16): plain, grouped heads, a kept count that is not a whole
+    # number of query tiles, and an odd number of query tiles (no split: the middle tile is alone)
+    (2, dict(batch=4, seq=2048), 0.5), (3, dict(batch=5, seq=2048), 0.5),
+    (2, dict(batch=4, seq=2048), 0.55), (2, dict(batch=4, seq=2048), 0.4),
+])
+def test_whole_path_when_the_last_round_is_split(ctx, wl):
+    i, changes, ratio = wl
+    w = synth.scaled(synth.workload(i), **changes)
+    _say("whole path, split last round %s %s r=%g" % (w.name, changes, ratio))
+    q, k, v, _ = synth.make_qkv(w)
+    check_whole_path(ctx, q, k, v, ratio)
+
+
 @pytest.mark.parametrize("case", [
     ("f32", 1, 4, 4, 257, 0.0, 1), ("bf16", 1, 4, 2, 257, 0.0, 1), ("f32", 1, 2, 2, 1, 0.5, 1),
     ("bf16", 2, 4, 4, 300, 0.99, 1), ("bf16", 1, 4, 4, 300, 0.5, 0), ("f32", 1, 4, 4, 300, 0.5, 64),
