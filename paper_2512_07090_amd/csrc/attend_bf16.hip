@@ -58,7 +58,6 @@ constexpr int kVStr = kHeadDim + 32;     // V tile row stride, elements (320 B)
 constexpr int kKTile = kBN * kKStr;      // elements per K tile
 constexpr int kVTile = kBN * kVStr;      // elements per V tile
 constexpr int kOStr = kHeadDim + 8;      // output staging row stride, elements
-constexpr int kShortGap = 3;             // zero rows written right after a query's row
 constexpr float kMaxSlack = 8.0f;        // running max may lag the true max by 2^8
 constexpr float kMasked = -1e30f;
 
@@ -129,6 +128,12 @@ __device__ __forceinline__ float add_bf16x2(unsigned w, float acc)
 {
     return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, w),
                                            __builtin_bit_cast(bf16x2, 0x3f803f80u), acc, false);
+}
+
+// 16 bytes to global memory with the non-temporal hint (the line is not kept in the L2)
+__device__ __forceinline__ void store_streaming(uint16_t* dst, uint4 v)
+{
+    __builtin_nontemporal_store(__builtin_bit_cast(u32x4, v), reinterpret_cast<u32x4*>(dst));
 }
 
 __device__ __forceinline__ void store_rows(Rows<2> r, uint16_t* dst, int step)
@@ -526,14 +531,6 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_bf16_kernel(
     // here, per item, instead of being carried in registers across the tile loop)
     int ln = lane;
     asm volatile("" : "+v"(ln));
-    // position of the next kept token after each query (n after the last one): the rows in
-    // between belong to filtered tokens and are written as zeros with the query's row
-    int qnext[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int nx = idx[min(lim[u] + 1, m_last)];
-        qnext[u] = lim[u] < m_last ? nx : d.n;
-    }
     uint16_t* os = smem + wave * (WQ * kOStr);  // [WQ queries][kOStr]
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -551,8 +548,7 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_bf16_kernel(
             }
     }
     __syncthreads();
-    // Every 16-lane group writes one query's row and, after it, the zero rows of the filtered
-    // positions up to the next kept token (the first kShortGap of them; longer gaps below).
+    // Every 16-lane group writes one query's row: four rows per store instruction.
     const uint4 zero4 = make_uint4(0, 0, 0, 0);
     uint16_t* const Oc = Ob + 8 * (ln & 15);  // this lane's 16-byte column
 #pragma unroll
@@ -561,25 +557,39 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_bf16_kernel(
         for (int it = 0; it < 8; ++it) {
             const int r = 4 * it + (ln >> 4);  // query row inside the sub-tile
             const int p = __shfl(qpos[u], r);    // its position, held by lane r
-            const int pn = __shfl(qnext[u], r);
             if (iw + 32 * u + r < m) {
                 const uint4 v = *reinterpret_cast<const uint4*>(os + (32 * u + r) * kOStr + 8 * (ln & 15));
-                *reinterpret_cast<uint4*>(Oc + (long long)p * d.os[2]) = v;
-                const int g_end = min(pn, p + 1 + kShortGap);
-                for (int g = p + 1; g < g_end; ++g) *reinterpret_cast<uint4*>(Oc + (long long)g * d.os[2]) = zero4;
+                store_streaming(Oc + (long long)p * d.os[2], v);
             }
         }
-    // long gaps, one at a time, four rows per store instruction
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int z0 = qpos[u] + 1 + kShortGap;
-        unsigned long long todo = __ballot(ln < 32 && iw + 32 * u + ln < m && z0 < qnext[u]);
-        while (todo) {
-            const int r = __builtin_ctzll(todo);
-            todo &= todo - 1;
-            const int ze = __shfl(qnext[u], r);
-            for (int g = __shfl(z0, r) + (ln >> 4); g < ze; g += 4)
-                *reinterpret_cast<uint4*>(Oc + (long long)g * d.os[2]) = zero4;
+    // The zero rows this wave owns: the filtered positions after its first query and before the
+    // first query of the next wave (n after the last kept token).  They are written densely, four
+    // rows per store instruction whatever the gaps look like: with z_i = the zero rows before
+    // query i (= position_i - position_0 - i, ascending), the k-th zero row sits at
+    // position_0 + 1 + k + #{i >= 1 : z_i <= k}, and the count is a ballot over the queries.
+    // All output stores are non-temporal: O is written once and never read here, and lines of O
+    // allocated in the L2 push out K / V tiles that other query tiles of the group still need.
+    static_assert(U == 1, "the dense zero-row writer assumes one 32-query sub-tile per wave");
+    {
+        const int n_valid = min(max(m - iw, 0), WQ);  // queries of this wave that exist
+        if (n_valid > 0) {
+            const int p_first = __builtin_amdgcn_readfirstlane(qpos[0]);
+            const int last_rank = iw + n_valid - 1;
+            const int p_end = last_rank < m_last ? idx[last_rank + 1] : d.n;  // uniform
+            const int n_zero = __builtin_amdgcn_readfirstlane(p_end - p_first - n_valid);
+            const int z_mine = qpos[0] - p_first - ln;  // meaningful for lanes 1 .. n_valid - 1
+            const bool counted = ln >= 1 && ln < n_valid;
+            const int grp = ln >> 4;
+            for (int k0 = 0; k0 < n_zero; k0 += 4) {
+                const int c0 = __popcll(__ballot(counted && z_mine <= k0));
+                const int c1 = __popcll(__ballot(counted && z_mine <= k0 + 1));
+                const int c2 = __popcll(__ballot(counted && z_mine <= k0 + 2));
+                const int c3 = __popcll(__ballot(counted && z_mine <= k0 + 3));
+                const int cnt = grp == 0 ? c0 : (grp == 1 ? c1 : (grp == 2 ? c2 : c3));
+                const int k = k0 + grp;
+                if (k < n_zero)
+                    store_streaming(Oc + (long long)(p_first + 1 + k + cnt) * d.os[2], zero4);
+            }
         }
     }
     // positions before the first kept token
