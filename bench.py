@@ -54,7 +54,7 @@ def read_traffic(name):
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":")[1]), "profiles/" + name
+                return float(line.split(":")[1].split()[0]), "profiles/" + name
     except OSError:
         pass
     return None, None

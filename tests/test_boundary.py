@@ -107,3 +107,20 @@ def test_tail_schedule_host_matches_oracle():
     for bad in ((0, 0.2, 0.5), (4, -0.1, 0.5), (4, 0.2, 0.0), (4, 0.2, 1.5)):
         with pytest.raises(B.TokfiltError):
             B.tf_tail_schedule(*bad)
+
+
+def test_bench_reads_the_traffic_of_every_committed_counter_summary():
+    """bench.py takes `roofline.traffic` from the counter summaries under profiles/: every
+    workload's attention and scoring summary must hold a figure it can read."""
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    if root not in sys.path:
+        sys.path.insert(0, root)
+    import bench
+    from paper_2512_07090_amd import synth
+    for w in synth.WORKLOADS:
+        att = "attend_f32" if w.dtype == "f32" else "attend_bf16"
+        for name in ("%s_%s_pmc.txt" % (att, w.name), "scan_score_%s_pmc.txt" % w.name):
+            value, source = bench.read_traffic(name)
+            assert value is not None and value > 1e5, name
+            assert source == "profiles/" + name
