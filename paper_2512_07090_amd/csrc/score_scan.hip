@@ -28,6 +28,9 @@ constexpr int kThreads = 256;
 constexpr int kR = 8;               // rows per thread per tile
 constexpr int kTile = 16 * kR;      // rows per tile
 
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
 template <typename T>
 struct Row8;
 
@@ -35,6 +38,12 @@ template <>
 struct Row8<uint16_t> {             // bf16 storage
     uint4 raw;
     __device__ __forceinline__ void load(const uint16_t* p) { raw = *reinterpret_cast<const uint4*>(p); }
+    // the same with the non-temporal hint: the line is not kept in the L2 after this read
+    __device__ __forceinline__ void load_streaming(const uint16_t* p)
+    {
+        const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+        raw = make_uint4(v[0], v[1], v[2], v[3]);
+    }
     __device__ __forceinline__ void zero() { raw = make_uint4(0, 0, 0, 0); }
     __device__ __forceinline__ void unpack(float* x) const
     {
@@ -66,6 +75,13 @@ struct Row8<float> {
         lo = *reinterpret_cast<const float4*>(p);
         hi = *reinterpret_cast<const float4*>(p + 4);
     }
+    __device__ __forceinline__ void load_streaming(const float* p)
+    {
+        const f32x4 a = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p));
+        const f32x4 b = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(p + 4));
+        lo = make_float4(a[0], a[1], a[2], a[3]);
+        hi = make_float4(b[0], b[1], b[2], b[3]);
+    }
     __device__ __forceinline__ void zero() { lo = hi = make_float4(0.f, 0.f, 0.f, 0.f); }
     __device__ __forceinline__ void unpack(float* x) const
     {
@@ -85,14 +101,21 @@ struct Row8<float> {
 // whatever the row: rows at or past t_end re-read row t_end - 1 (t_end >= 1) and are zeroed by
 // clear_rows_past() once they are used, so that no load sits under a branch and the compiler
 // can count how many loads are still in flight when it waits for a tile.
-template <typename T>
+// STREAM: the scan reads every row once; loaded with the non-temporal hint, its stream (0.5 GB on
+// the benchmark shape) does not displace what the other kernels of the step, and the next launch
+// of the scan, find in the caches.  The totals pass, whose rows the scan reads again right
+// after, loads them the ordinary way.
+template <bool STREAM, typename T>
 __device__ __forceinline__ void load_tile(Row8<T>* rows, const T* X, long long s_t, int t_first,
                                           int t_end, int col)
 {
 #pragma unroll
     for (int r = 0; r < kR; ++r) {
         const int t = min(t_first + r, t_end - 1);
-        rows[r].load(X + (long long)t * s_t + col);
+        if (STREAM)
+            rows[r].load_streaming(X + (long long)t * s_t + col);
+        else
+            rows[r].load(X + (long long)t * s_t + col);
     }
 }
 template <typename T>
@@ -132,7 +155,7 @@ __global__ __launch_bounds__(kThreads) void segment_totals_kernel(
     float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     for (int t0 = t_begin; t0 < t_end; t0 += kTile) {
         Row8<T> rows[kR];
-        load_tile(rows, X, s_t, t0 + rg * kR, t_end, 8 * l);
+        load_tile<false>(rows, X, s_t, t0 + rg * kR, t_end, 8 * l);
         if (t0 + kTile > t_end) clear_rows_past(rows, t0 + rg * kR, t_end);
 #pragma unroll
         for (int r = 0; r < kR; ++r) {
@@ -162,7 +185,8 @@ __global__ __launch_bounds__(kThreads) void segment_totals_kernel(
 // no weight left); no totals pass is needed.
 // first_tensor: 0 to walk K and V, or, with a single tensor (key-only / value-only scores),
 // the tensor to walk (0 = K, 1 = V).
-template <typename T, bool EMA, bool INCL>
+// STREAM: see load_tile (chosen by the host from the size of K and V).
+template <typename T, bool EMA, bool INCL, bool STREAM>
 __global__ __launch_bounds__(kThreads) void scan_score_kernel(
     const T* __restrict__ K, const T* __restrict__ V, long long s_b, long long s_h, long long s_t,
     int BH, int Hkv, int n, int nseg, int seg_len, const float* __restrict__ seg_tot,
@@ -202,8 +226,8 @@ __global__ __launch_bounds__(kThreads) void scan_score_kernel(
     }
 
     Row8<T> buf0[kR], buf1[kR], buf2[kR];
-    load_tile(buf0, X, s_t, t_begin + rg * kR, t_end, 8 * l);
-    load_tile(buf1, X, s_t, t_begin + kTile + rg * kR, t_end, 8 * l);
+    load_tile<STREAM>(buf0, X, s_t, t_begin + rg * kR, t_end, 8 * l);
+    load_tile<STREAM>(buf1, X, s_t, t_begin + kTile + rg * kR, t_end, 8 * l);
 
     int parity = 0;
     auto process = [&](Row8<T>* rows, int t0, bool first_tile) {
@@ -322,13 +346,13 @@ __global__ __launch_bounds__(kThreads) void scan_score_kernel(
 
     // two tiles in flight while a third is processed (rows past the end load as zeros)
     for (int t0 = t_begin; t0 < t_end; t0 += 3 * kTile) {
-        load_tile(buf2, X, s_t, t0 + 2 * kTile + rg * kR, t_end, 8 * l);
+        load_tile<STREAM>(buf2, X, s_t, t0 + 2 * kTile + rg * kR, t_end, 8 * l);
         process(buf0, t0, t0 == 0);
         if (t0 + kTile >= t_end) break;
-        load_tile(buf0, X, s_t, t0 + 3 * kTile + rg * kR, t_end, 8 * l);
+        load_tile<STREAM>(buf0, X, s_t, t0 + 3 * kTile + rg * kR, t_end, 8 * l);
         process(buf1, t0 + kTile, false);
         if (t0 + 2 * kTile >= t_end) break;
-        load_tile(buf1, X, s_t, t0 + 4 * kTile + rg * kR, t_end, 8 * l);
+        load_tile<STREAM>(buf1, X, s_t, t0 + 4 * kTile + rg * kR, t_end, 8 * l);
         process(buf2, t0 + 2 * kTile, false);
     }
 }
@@ -363,6 +387,15 @@ static int ema_warm_rows(float gamma)
     return (int)((((long long)rows + kTile - 1) / kTile) * kTile);
 }
 
+template <typename T, bool EMA, bool INCL, typename... Args>
+static void launch_scan(bool stream_loads, int grid, hipStream_t s, Args... args)
+{
+    if (stream_loads)
+        scan_score_kernel<T, EMA, INCL, true><<<dim3(grid), dim3(kThreads), 0, s>>>(args...);
+    else
+        scan_score_kernel<T, EMA, INCL, false><<<dim3(grid), dim3(kThreads), 0, s>>>(args...);
+}
+
 template <typename T>
 static hipError_t launch_score_t(const Dims& d, const T* K, const T* V, float* sim_k,
                                  float* sim_v, float* seg_tot, int tensors, int anchor,
@@ -375,6 +408,11 @@ static hipError_t launch_score_t(const Dims& d, const T* K, const T* V, float* s
     const int chains = n_tensors * BH;
     const int inclusive = anchor >> 1;  // bit 1 of `anchor`: the anchor of a row includes the row
     anchor &= 1;
+    // Tensors that together exceed the last-level cache (256 MB Infinity Cache) are streamed past
+    // the L2: measured on whole steps, workload 2 (537 MB) -2.6 %, workload 3 (336 MB) -1.2 %;
+    // below that size the later kernels find the rows in the caches and streaming costs
+    // (workload 4, 67 MB: +0.7 %; workload 1, 17 MB: +12 %).
+    const bool stream_loads = (double)chains * d.n * kHeadDim * sizeof(T) > 256.0 * 1024 * 1024;
     if (anchor == 1) {
         // segments only if their warm-up is at most as long as they are
         const int warm = ema_warm_rows(gamma);
@@ -386,13 +424,13 @@ static hipError_t launch_score_t(const Dims& d, const T* K, const T* V, float* s
             p = ScorePlan{(tiles + tiles_per_seg - 1) / tiles_per_seg, tiles_per_seg * kTile};
         }
         if (inclusive)
-            scan_score_kernel<T, true, true><<<dim3(chains * p.nseg), dim3(kThreads), 0, s>>>(
-                K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k,
-                sim_v, first_tensor, gamma, warm);
+            launch_scan<T, true, true>(stream_loads, chains * p.nseg, s, K, V, d.kvs[0], d.kvs[1], d.kvs[2],
+                                       BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k, sim_v,
+                                       first_tensor, gamma, warm);
         else
-            scan_score_kernel<T, true, false><<<dim3(chains * p.nseg), dim3(kThreads), 0, s>>>(
-                K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k,
-                sim_v, first_tensor, gamma, warm);
+            launch_scan<T, true, false>(stream_loads, chains * p.nseg, s, K, V, d.kvs[0], d.kvs[1], d.kvs[2],
+                                        BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k, sim_v,
+                                        first_tensor, gamma, warm);
         return hipGetLastError();
     }
     if (p.nseg > 1) {
@@ -401,13 +439,13 @@ static hipError_t launch_score_t(const Dims& d, const T* K, const T* V, float* s
             first_tensor);
     }
     if (inclusive)
-        scan_score_kernel<T, false, true><<<dim3(chains * p.nseg), dim3(kThreads), 0, s>>>(
-            K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k,
-            sim_v, first_tensor, 0.f, 0);
+        launch_scan<T, false, true>(stream_loads, chains * p.nseg, s, K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH,
+                                    d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k, sim_v, first_tensor,
+                                    0.f, 0);
     else
-        scan_score_kernel<T, false, false><<<dim3(chains * p.nseg), dim3(kThreads), 0, s>>>(
-            K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH, d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k,
-            sim_v, first_tensor, 0.f, 0);
+        launch_scan<T, false, false>(stream_loads, chains * p.nseg, s, K, V, d.kvs[0], d.kvs[1], d.kvs[2], BH,
+                                     d.Hkv, d.n, p.nseg, p.seg_len, seg_tot, sim_k, sim_v, first_tensor,
+                                     0.f, 0);
     return hipGetLastError();
 }
 
