@@ -570,6 +570,32 @@ def test_full_size_workload_2_every_row(ctx):
     _full_size_case(ctx, synth.workload(1), (0.5, 0.25))
 
 
+@pytest.mark.parametrize("variant", [
+    dict(ema_gamma=0.9), dict(anchor_inclusive=True), dict(ema_gamma=0.9, anchor_inclusive=True),
+])
+def test_full_size_workload_2_scores_of_the_other_anchors(ctx, variant):
+    """The other anchor kinds at the full benchmark size (where K and V exceed the last-level
+    cache and the scan streams them): per-head cosines and fused scores against the oracle."""
+    w = synth.workload(1)
+    _say("full size %s scores %s" % (w.name, variant))
+    q, k, v, _ = synth.make_qkv(w)
+    p = B.make_params(tuple(q.shape), tuple(k.shape), q.dtype, 0.5, **variant)
+    buf = B.Buffers(p, "cuda:0", with_sims=True)
+    buf.sim_k.fill_(7.0)
+    buf.sim_v.fill_(7.0)
+    ctx.tf_score(p, k.cuda(), v.cuda(), buf.fused, buf.sim_k, buf.sim_v, buf.ws)
+    torch.cuda.synchronize()
+    gamma, inclusive = variant.get("ema_gamma"), variant.get("anchor_inclusive", False)
+    if gamma is None:
+        ck, cv = oracle.anchor_cosine(k, inclusive=inclusive), oracle.anchor_cosine(v, inclusive=inclusive)
+    else:
+        ck = oracle.anchor_cosine_ema(k, gamma, inclusive=inclusive)
+        cv = oracle.anchor_cosine_ema(v, gamma, inclusive=inclusive)
+    assert_scores_close(buf.sim_k.cpu().numpy(), ck, "sim_k")
+    assert_scores_close(buf.sim_v.cpu().numpy(), cv, "sim_v")
+    assert_scores_close(buf.fused.cpu().numpy(), oracle.fuse(ck, cv), "fused")
+
+
 def test_full_size_workload_3_split_noise_heads(ctx):
     _full_size_case(ctx, synth.workload(2), (0.5,))
 
