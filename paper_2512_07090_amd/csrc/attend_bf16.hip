@@ -169,7 +169,10 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_bf16_kernel(
     __shared__ __attribute__((aligned(16))) uint16_t smem[2 * kKTile + 2 * kVTile];
     uint16_t* const k_lds = smem;               // 2 stages of K
     uint16_t* const v_lds = smem + 2 * kKTile;  // 2 stages of V
-    static_assert(kBM * kOStr <= 2 * kKTile + 2 * kVTile, "output staging must fit");
+    // Output staging of its own (145 KB of LDS in all): a wave stages and writes its rows without
+    // a workgroup barrier on either side, so the waves leave an item, and start on the next
+    // item's first loads, as each gets there.
+    __shared__ __attribute__((aligned(16))) uint16_t ostage[kBM * kOStr];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -526,12 +529,12 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_bf16_kernel(
 #undef TF_STORE_ROWS
 #undef TF_COPY_POS
 
-    // normalise, transpose through LDS (all tiles are consumed) and write whole rows
+    // normalise, transpose through LDS and write whole rows
     // (the lane number goes through an opaque move so that the addresses below are formed
     // here, per item, instead of being carried in registers across the tile loop)
     int ln = lane;
     asm volatile("" : "+v"(ln));
-    uint16_t* os = smem + wave * (WQ * kOStr);  // [WQ queries][kOStr]
+    uint16_t* os = ostage + wave * (WQ * kOStr);  // [WQ queries][kOStr], this wave's alone
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const float l_mine = l_run[u] + l_alt[u];
@@ -547,7 +550,11 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_bf16_kernel(
                 *reinterpret_cast<bf16x4*>(os + (32 * u + (ln & 31)) * kOStr + 32 * dt + 8 * v4 + 4 * (ln >> 5)) = o4;
             }
     }
-    __syncthreads();
+    // the rows are read back by other lanes of this wave only: LDS operations of one wave
+    // complete in order, the compiler must just not move them across this point
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
     // Every 16-lane group writes one query's row: four rows per store instruction.
     const uint4 zero4 = make_uint4(0, 0, 0, 0);
     uint16_t* const Oc = Ob + 8 * (ln & 15);  // this lane's 16-byte column
@@ -597,7 +604,8 @@ __global__ __launch_bounds__(64 * NW, 2) void attend_bf16_kernel(
         const int ze = __shfl(qpos[0], 0);
         for (int g = ln >> 4; g < ze; g += 4) *reinterpret_cast<uint4*>(Oc + (long long)g * d.os[2]) = zero4;
     }
-    __syncthreads();  // the staging area becomes tile stages again
+    // (no barrier here: the last tile-loop iteration ended with one, after which nobody reads a
+    // tile stage, and the staging area is not shared)
     }  // items
 }
 
